@@ -1,0 +1,81 @@
+"""Pins of oracle/perf_model.py to the numbers and rules the paper prints.  CPU only."""
+import json
+import os
+
+import pytest
+
+from oracle import perf_model as pm
+
+G = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "paper_numbers.json")))
+
+
+def test_phi_reproduces_quoted_numbers():
+    # M*N*K = 1024^3 with M = N (Fig. 2 caption): K = 1024 -> M = N = 1024, tile size 256.
+    assert int(pm.phi(256, 256, 1024)) == G["phi_K1024_tile256"]["value"]
+    assert round(pm.phi(256, 256, 1)) == G["phi_K1_tile256"]["value"]
+    # the printed expression does not give them (the discrepancy that phi() resolves)
+    assert round(pm.phi_printed(256, 256, 1024)) == 205 and round(pm.phi_printed(256, 256, 1)) == 1
+    # closed-form special case: cubic tile T=K -> 2T^3 / 3T^2
+    assert pm.phi(96, 96, 96) == pytest.approx(2 * 96 / 3)
+
+
+def test_search_space_size():
+    assert len(pm.deep_tilings()) == G["deep_tilings"]["value"]
+    assert len(set(pm.deep_tilings())) == 24 and "mhnk" in pm.deep_tilings()
+    assert len(pm.flat_tilings()) == G["flat_tilings"]["value"]
+    assert pm.n_candidates(1024, 1024, 512, 512) == G["n_candidates_M1024_N1024_K512_H512"]["value"]
+
+
+def test_hoisting_factors_of_mhnk():
+    ext = {"m": 8, "h": 3, "n": 5, "k": 4}
+    # default association: every statement of C_C in m,h,n,k; those of C_E in m,h,n
+    assert pm.trips("mhnk", "C_C", ext) == 8 * 3 * 5 * 4
+    assert pm.trips("mhnk", "C_E", ext) == 8 * 3 * 5
+    assert pm.trips("mhnk", "L_A", ext, hoist=False) == 8 * 3 * 5 * 4
+    assert pm.trips("mhnk", "S_E", ext, hoist=False) == 8 * 3 * 5
+    # S_E moved to the scope of h: saves the extent of the loop it leaves
+    assert pm.trips("mhnk", "S_E", ext) == 8 * 3
+    # L_A stays under k while k > 1 ...
+    assert pm.trips("mhnk", "L_A", ext) == 8 * 3 * 5 * 4
+    # ... and is governed by m alone once k has extent 1: a factor h*n fewer loads
+    ext1 = dict(ext, k=1)
+    before = pm.trips("mhnk", "L_A", ext1, drop_unit_loops=False)
+    after = pm.trips("mhnk", "L_A", ext1)
+    assert after == 8 and before == after * ext["h"] * ext["n"]
+    # L_B is indexed by k and n: always innermost in mhnk; L_D sits at n
+    assert pm.trips("mhnk", "L_B", ext) == 8 * 3 * 5 * 4
+    assert pm.trips("mhnk", "L_D", ext) == 8 * 3 * 5
+    # mhnk and mnkh with h of extent 1 move the same data (same per-block expression nk)
+    ext2 = dict(ext1, h=1)
+    for s in ("L_A", "L_B", "L_D", "S_E", "C_C", "C_E"):
+        assert pm.trips("mhnk", s, ext2) == pm.trips("mnkh", s, ext2)
+
+
+def test_eq1_shared_memory_and_rule3():
+    tiles = {"m": 64, "n": 32, "k": 16, "h": 48}
+    assert pm.shm_estm(tiles) == 64 * 16 + 16 * 32 + 64 * 32 + 32 * 48 + 64 * 48
+    assert pm.shm_estm(tiles, "BD") == 16 * 32 + 32 * 48
+    assert pm.padding_ok(1024, 128) and not pm.padding_ok(1024, 96)       # power of two: no padding
+    assert pm.padding_ok(1000, 128) and not pm.padding_ok(768, 512)       # 2.4 % ok, 33 % not
+    assert pm.padding_ok(80, 16) and not pm.padding_ok(80, 32)
+
+
+def test_eq2_to_5_hand_evaluated():
+    # dims 512/512/64/64, tiles 64 everywhere, one batch, 2-byte elements, W = 1e12 B/s,
+    # P = 1e14 FLOP/s, 100 compute units.  Extents: m = n = 8, k = h = 1.
+    dims = {"m": 512, "n": 512, "k": 64, "h": 64}
+    tiles = {"m": 64, "n": 64, "k": 64, "h": 64}
+    r = pm.estimate("mhnk", dims, tiles, batch=1, elem_bytes=2, W=1e12, P=1e14, n_units=100)
+    assert r["mem_bytes"] == {"L_A": 65536, "L_B": 524288, "L_D": 524288, "S_E": 65536}
+    assert r["model_bytes"] == 1179648 and r["compulsory_bytes"] == 2 * (3 * 512 * 64 + 64 * 512)
+    assert r["flops"] == 67108864 and r["n_block"] == 8
+    assert r["t_mem"] == pytest.approx(1.179648e-6, rel=1e-15)
+    assert r["t_comp"] == pytest.approx(6.7108864e-7, rel=1e-15)
+    assert r["alpha"] == 13.5
+    assert r["t_estm"] == pytest.approx(2.498494464e-5, rel=1e-12)
+    # whole-problem tiles: one block, compulsory traffic only, alpha = 101
+    one = pm.estimate("mhnk", dims, dims, batch=1, elem_bytes=2, W=1e12, P=1e14, n_units=100)
+    assert one["model_bytes"] == one["compulsory_bytes"] and one["alpha"] == 101
+    # split bandwidths: re-read bytes charged at the faster level
+    s = pm.estimate("mhnk", dims, tiles, 1, 2, W=1e12, P=1e14, n_units=100, W_reread=4e12)
+    assert s["t_mem"] == pytest.approx(262144 / 1e12 + (1179648 - 262144) / 4e12, rel=1e-15)
