@@ -1,0 +1,127 @@
+/*
+ * mcf -- fused memory-bound compute-intensive (MBCI) operator chains on AMD MI355X (gfx950).
+ *
+ * C ABI of the library.  Plain C, no exceptions cross this boundary; every call returns an
+ * mcf_status.  The operation is the two-GEMM chain of MCFuser (arXiv 2506.22169):
+ *
+ *   Sec. III-A (GEMM chain C = A x B, E = C x D) and Sec. VI-B1 (batched form):
+ *       C[b] = A[b] . B[b]        A[b]: M x K,  B[b]: K x N
+ *       E[b] = C[b] . D[b]        D[b]: N x L   (the paper's H is called L here)
+ *   Sec. VI-B2 (self-attention module: the same chain with a softmax between the GEMMs):
+ *       E[b] = softmax_rows(scale * A[b] . B[b]) . D[b]
+ *
+ * computed by ONE kernel in which the intermediate C (or S/P) lives in registers only and
+ * never reaches device memory (Sec. II-B "Redundant Memory Access", Sec. III-B).  The tile
+ * shape is taken from the analytical model of Sec. IV-A, eq. (2)-(5), under the on-chip
+ * memory rule of Sec. III-C, eq. (1), instead of a search.
+ *
+ * Memory: A, B, D, E are DEVICE pointers owned by the caller (e.g. PyTorch allocations).
+ * The mcf_problem / mcf_tiles structs are HOST memory.  The library allocates nothing on the
+ * device, never synchronises, and launches asynchronously on the caller's stream.
+ */
+#ifndef MCF_H
+#define MCF_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { MCF_F16 = 0, MCF_BF16 = 1 } mcf_dtype;
+
+typedef enum {
+    MCF_OK = 0,
+    MCF_EINVAL = 1,       /* null pointer, negative dimension, bad stride, aliasing, bad tiles   */
+    MCF_EUNSUPPORTED = 2, /* no kernel variant covers this shape / dtype / layout                */
+    MCF_EALIGN = 3,       /* a base pointer or a leading stride breaks the 16-byte requirement   */
+    MCF_ELAUNCH = 4       /* the HIP runtime rejected the launch (hipGetLastError)               */
+} mcf_status;
+
+/*
+ * Problem statement (Sec. VI-B1: (batch,M,K) x (batch,K,N), then (batch,M,N) x (batch,N,L)).
+ * Strides are in ELEMENTS, ordered {batch, row, col}; an all-zero triple means packed
+ * row-major.  Layout requirements of the kernels:
+ *   A: col stride 1 (K contiguous);  D, E: col stride 1 (L contiguous);
+ *   B: either col stride 1 ([b,K,N], N contiguous: the GEMM-chain layout) or row stride 1
+ *      ([b,N,K] handed over as {N*K, 1, K}: the key matrix of attention, K contiguous).
+ *   Every non-unit row stride and every batch stride is a multiple of 8 elements; for
+ *   N-contiguous B, N itself is a multiple of 8.  Base pointers are 16-byte aligned.
+ * Supported here: K, L in {32, 64, 128}; any batch, M >= 0, N >= 0 (N >= 1 with softmax).
+ * in_dtype is the type of A, B, D; out_dtype that of E and must equal in_dtype.
+ * Both GEMMs accumulate in fp32; C (or P) is rounded once to in_dtype between them.
+ */
+typedef struct mcf_problem {
+    int64_t batch, M, K, N, L;
+    int32_t in_dtype, out_dtype; /* mcf_dtype */
+    int64_t a_stride[3], b_stride[3], d_stride[3], e_stride[3];
+} mcf_problem;
+
+/*
+ * A tile choice and the model terms it was ranked by.  Tiling expression per block is the
+ * paper's "nk" sub-expression with T_K = K and T_L = L (so the k and h loops have extent 1
+ * and L_A / S_E are hoisted out of the n loop, Sec. III-B):
+ *     block <-> (batch, m-tile);   for n-tile: { L_B, L_D -> LDS; C_C; [softmax]; C_E };  S_E
+ * tm = 32 * mb * rg rows per block (rg wave row-groups, each wave owning 32*mb rows),
+ * tn = 32 * ns columns per n-iteration (ns waves side by side in n), waves = rg * ns.
+ */
+typedef struct mcf_tiles {
+    int32_t tm, tn, tk, tl;   /* tile sizes T_M, T_N, T_K (= K), T_L (= L)                       */
+    int32_t mb, rg, ns;       /* 32-row blocks per wave, wave row-groups, waves across n         */
+    int32_t waves;            /* rg * ns, 64 lanes each                                          */
+    int32_t lds_bytes;        /* eq. (1) restricted to the tiles held in LDS (B, D; 2 stages)    */
+    int32_t vgpr_est;         /* eq. (1) restricted to the tiles held in registers (A, C, E)     */
+    int64_t blocks;           /* N_block of eq. (5)                                              */
+    int64_t compulsory_bytes; /* A, B, D read once + E written once                              */
+    int64_t model_bytes;      /* numerator of eq. (3): sum of tile bytes x trip counts           */
+    int64_t flops;            /* numerator of eq. (4), padding included                          */
+    double t_mem_s, t_comp_s, alpha, t_est_s; /* eq. (3), (4), (5), (2)                          */
+} mcf_tiles;
+
+/*
+ * Tile picker (Sec. IV-A eq. (2)-(5), Sec. III-C Rules 3-4).  Host only: needs no GPU.
+ * Enumerates the kernel variants built into the library that cover (K, L, dtype, layout),
+ * drops those that break the LDS / register budget or the padding rule, and returns the one
+ * with the smallest t_est.  out is host memory.  MCF_EUNSUPPORTED if nothing covers the shape.
+ */
+int mcf_pick_tiles(const mcf_problem *problem, int softmax, mcf_tiles *out);
+
+/*
+ * Evaluate the model for a caller-chosen (mb, rg, ns) instead of picking: fills every other
+ * field of *tiles.  MCF_EUNSUPPORTED if no built variant has that shape, MCF_EINVAL if it
+ * breaks a budget.  Host only.
+ */
+int mcf_eval_tiles(const mcf_problem *problem, int softmax, mcf_tiles *tiles);
+
+/* Number of built kernel variants and their (mb, rg, ns) for the shape; host only.
+ * Writes up to cap triples into mb_rg_ns (3 ints each) and returns the total count. */
+int mcf_list_variants(const mcf_problem *problem, int softmax, int32_t *mb_rg_ns, int cap);
+
+/*
+ * E = (A . B) . D   (Sec. III-A).  Device pointers; tiles_or_null == NULL means
+ * mcf_pick_tiles() decides, otherwise only its mb, rg, ns fields are read.  hip_stream is a
+ * hipStream_t (NULL = the default stream).  E must not overlap A, B or D.  batch, M or L of
+ * zero is a no-op; N == 0 writes zeros.
+ */
+int mcf_gemm_chain(const mcf_problem *problem, const void *A, const void *B, const void *D,
+                   void *E, const mcf_tiles *tiles_or_null, void *hip_stream);
+
+/*
+ * E = softmax_rows(scale * A . B) . D   (Sec. VI-B2; softmax along n, no mask).  The kernel
+ * uses the online max / sum recurrence over n-tiles, which equals the two-pass definition up
+ * to rounding.  Same argument rules as mcf_gemm_chain; N == 0 is MCF_EINVAL.
+ */
+int mcf_softmax_gemm_chain(const mcf_problem *problem, float scale, const void *A,
+                           const void *B, const void *D, void *E,
+                           const mcf_tiles *tiles_or_null, void *hip_stream);
+
+/* Human-readable name of a status code (static storage). */
+const char *mcf_status_string(int status);
+
+/* Text of the last HIP error seen by this thread inside the library, "" if none. */
+const char *mcf_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MCF_H */

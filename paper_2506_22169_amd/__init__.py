@@ -1,0 +1,7 @@
+"""MI355X-native fused MBCI operator chains (MCFuser, arXiv 2506.22169): thin Python binding
+over the C ABI of libmcf.so.  Every step of the path runs in the HIP kernels; this package
+only marshals arguments.  Importing works without the built library, calling does not."""
+from .binding import (  # noqa: F401
+    McfError, Problem, Tiles, gemm_chain, softmax_gemm_chain, pick_tiles, eval_tiles,
+    list_variants, library_path, load_library, status_string,
+)

@@ -1,0 +1,203 @@
+"""ctypes binding of include/mcf.h (same names, argument marshalling only).
+
+torch is used for device memory and streams: tensors come in as torch CUDA(=HIP) tensors,
+their data pointers, strides and the current stream are handed to the C ABI.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmcf.so")
+_lib = None
+
+MCF_F16, MCF_BF16 = 0, 1
+MCF_OK = 0
+
+
+class McfError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(text)
+        self.status = status
+
+
+class Problem(ctypes.Structure):
+    """struct mcf_problem"""
+    _fields_ = [("batch", ctypes.c_int64), ("M", ctypes.c_int64), ("K", ctypes.c_int64),
+                ("N", ctypes.c_int64), ("L", ctypes.c_int64),
+                ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
+                ("a_stride", ctypes.c_int64 * 3), ("b_stride", ctypes.c_int64 * 3),
+                ("d_stride", ctypes.c_int64 * 3), ("e_stride", ctypes.c_int64 * 3)]
+
+
+class Tiles(ctypes.Structure):
+    """struct mcf_tiles"""
+    _fields_ = [("tm", ctypes.c_int32), ("tn", ctypes.c_int32), ("tk", ctypes.c_int32), ("tl", ctypes.c_int32),
+                ("mb", ctypes.c_int32), ("rg", ctypes.c_int32), ("ns", ctypes.c_int32),
+                ("waves", ctypes.c_int32), ("lds_bytes", ctypes.c_int32), ("vgpr_est", ctypes.c_int32),
+                ("blocks", ctypes.c_int64), ("compulsory_bytes", ctypes.c_int64),
+                ("model_bytes", ctypes.c_int64), ("flops", ctypes.c_int64),
+                ("t_mem_s", ctypes.c_double), ("t_comp_s", ctypes.c_double),
+                ("alpha", ctypes.c_double), ("t_est_s", ctypes.c_double)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libmcf.so; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise McfError(-1, f"{_LIB_PATH} is missing: build it with "
+                           "`python -m paper_2506_22169_amd.build` (hipcc, gfx950); there is no fallback")
+    lib = ctypes.CDLL(_LIB_PATH)
+    PP, TP, vp = ctypes.POINTER(Problem), ctypes.POINTER(Tiles), ctypes.c_void_p
+    lib.mcf_pick_tiles.argtypes = [PP, ctypes.c_int, TP]
+    lib.mcf_eval_tiles.argtypes = [PP, ctypes.c_int, TP]
+    lib.mcf_list_variants.argtypes = [PP, ctypes.c_int, ctypes.POINTER(ctypes.c_int32), ctypes.c_int]
+    lib.mcf_gemm_chain.argtypes = [PP, vp, vp, vp, vp, TP, vp]
+    lib.mcf_softmax_gemm_chain.argtypes = [PP, ctypes.c_float, vp, vp, vp, vp, TP, vp]
+    for f in (lib.mcf_pick_tiles, lib.mcf_eval_tiles, lib.mcf_list_variants, lib.mcf_gemm_chain,
+              lib.mcf_softmax_gemm_chain):
+        f.restype = ctypes.c_int
+    lib.mcf_status_string.argtypes = [ctypes.c_int]
+    lib.mcf_status_string.restype = ctypes.c_char_p
+    lib.mcf_last_error.argtypes = []
+    lib.mcf_last_error.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def status_string(status):
+    return load_library().mcf_status_string(int(status)).decode()
+
+
+def _check(status):
+    if status != MCF_OK:
+        lib = load_library()
+        extra = lib.mcf_last_error().decode()
+        raise McfError(status, status_string(status) + (f" ({extra})" if extra else ""))
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.float16:
+        return MCF_F16
+    if t.dtype == torch.bfloat16:
+        return MCF_BF16
+    raise McfError(2, f"unsupported dtype {t.dtype}")
+
+
+def make_problem(batch, M, K, N, L, dtype, a_stride=None, b_stride=None, d_stride=None, e_stride=None):
+    """mcf_problem from plain numbers; dtype is 'f16' / 'bf16' or an mcf_dtype code."""
+    code = {"f16": MCF_F16, "bf16": MCF_BF16}.get(dtype, dtype)
+    p = Problem(batch, M, K, N, L, code, code)
+    for name, s in (("a_stride", a_stride), ("b_stride", b_stride), ("d_stride", d_stride), ("e_stride", e_stride)):
+        if s is not None:
+            setattr(p, name, (ctypes.c_int64 * 3)(*s))
+    return p
+
+
+def _problem_from_tensors(A, B, D, E):
+    if A.dim() != 3 or B.dim() != 3 or D.dim() != 3 or E.dim() != 3:
+        raise McfError(1, "A, B, D, E must be 3-d [batch, rows, cols]")
+    b, M, K = A.shape
+    b2, K2, N = B.shape
+    b3, N2, L = D.shape
+    if not (b == b2 == b3 and K == K2 and N == N2 and tuple(E.shape) == (b, M, L)):
+        raise McfError(1, f"shape mismatch A{tuple(A.shape)} B{tuple(B.shape)} D{tuple(D.shape)} E{tuple(E.shape)}")
+    if not (A.dtype == B.dtype == D.dtype == E.dtype):
+        raise McfError(1, "A, B, D, E must share one dtype")
+    if not (A.is_cuda and B.is_cuda and D.is_cuda and E.is_cuda):
+        raise McfError(1, "A, B, D, E must be device tensors")
+    code = _dtype_code(A)
+
+    def st(t):
+        # an empty tensor has no meaningful strides (None = packed); neither has a
+        # dimension of extent <= 1: give it the packed one
+        if t.numel() == 0:
+            return None
+        s = list(t.stride())
+        shape = list(t.shape)
+        if shape[2] <= 1:
+            s[2] = 1
+        if shape[1] <= 1:
+            s[1] = max(shape[2], 1) * s[2] if s[2] == 1 else 1
+        if shape[0] <= 1:
+            s[0] = 0
+        return s
+    return make_problem(b, M, K, N, L, code, st(A), st(B), st(D), st(E))
+
+
+def _stream_ptr(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _tiles_arg(tiles):
+    if tiles is None:
+        return None
+    if isinstance(tiles, Tiles):
+        return ctypes.byref(tiles)
+    mb, rg, ns = tiles
+    t = Tiles()
+    t.mb, t.rg, t.ns = mb, rg, ns
+    return ctypes.byref(t)
+
+
+def _run(softmax, scale, A, B, D, out, tiles, stream):
+    import torch
+    lib = load_library()
+    if out is None:
+        out = torch.empty((A.shape[0], A.shape[1], D.shape[2]), dtype=A.dtype, device=A.device)
+    p = _problem_from_tensors(A, B, D, out)
+    args = [ctypes.c_void_p(A.data_ptr()), ctypes.c_void_p(B.data_ptr()), ctypes.c_void_p(D.data_ptr()),
+            ctypes.c_void_p(out.data_ptr()), _tiles_arg(tiles), _stream_ptr(stream)]
+    if softmax:
+        _check(lib.mcf_softmax_gemm_chain(ctypes.byref(p), ctypes.c_float(scale), *args))
+    else:
+        _check(lib.mcf_gemm_chain(ctypes.byref(p), *args))
+    return out
+
+
+def gemm_chain(A, B, D, out=None, tiles=None, stream=None):
+    """mcf_gemm_chain: E = (A . B) . D on device tensors A[b,M,K], B[b,K,N] (any of the two
+    supported layouts, e.g. a transposed view of [b,N,K]), D[b,N,L].  tiles: None (picker),
+    a Tiles struct or an (mb, rg, ns) triple."""
+    return _run(False, 1.0, A, B, D, out, tiles, stream)
+
+
+def softmax_gemm_chain(A, B, D, scale, out=None, tiles=None, stream=None):
+    """mcf_softmax_gemm_chain: E = softmax_rows(scale * A . B) . D."""
+    return _run(True, float(scale), A, B, D, out, tiles, stream)
+
+
+def pick_tiles(problem, softmax=False):
+    """mcf_pick_tiles on an mcf_problem (see make_problem); host only."""
+    t = Tiles()
+    _check(load_library().mcf_pick_tiles(ctypes.byref(problem), int(bool(softmax)), ctypes.byref(t)))
+    return t
+
+
+def eval_tiles(problem, mb, rg, ns, softmax=False):
+    """mcf_eval_tiles: model terms of a caller-chosen wave arrangement; host only."""
+    t = Tiles()
+    t.mb, t.rg, t.ns = mb, rg, ns
+    _check(load_library().mcf_eval_tiles(ctypes.byref(problem), int(bool(softmax)), ctypes.byref(t)))
+    return t
+
+
+def list_variants(problem, softmax=False):
+    """mcf_list_variants: (mb, rg, ns) of every built kernel variant that covers the shape."""
+    lib = load_library()
+    n = lib.mcf_list_variants(ctypes.byref(problem), int(bool(softmax)), None, 0)
+    buf = (ctypes.c_int32 * (3 * max(n, 1)))()
+    lib.mcf_list_variants(ctypes.byref(problem), int(bool(softmax)), buf, n)
+    return [tuple(buf[3 * i:3 * i + 3]) for i in range(n)]

@@ -1,0 +1,148 @@
+// C ABI entry points: argument validation, tile choice, variant dispatch, launch.
+#include <hip/hip_runtime_api.h>
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "mcf_internal.h"
+
+namespace mcf {
+
+static thread_local char g_last_error[256] = "";
+void set_last_error(const char *msg) { snprintf(g_last_error, sizeof(g_last_error), "%s", msg ? msg : ""); }
+
+static bool all_zero(const int64_t s[3]) { return s[0] == 0 && s[1] == 0 && s[2] == 0; }
+
+static void packed(int64_t out[3], int64_t rows, int64_t cols) {
+    out[0] = rows * cols; out[1] = cols; out[2] = 1;
+}
+
+int decode_layout(const mcf_problem *p, Layout *o) {
+    if (p->in_dtype != MCF_F16 && p->in_dtype != MCF_BF16) return MCF_EUNSUPPORTED;
+    if (p->out_dtype != p->in_dtype) return MCF_EUNSUPPORTED;
+    if (!(p->K == 32 || p->K == 64 || p->K == 128) || p->L != p->K) return MCF_EUNSUPPORTED;
+    if (p->M >= (1ll << 31) - 512 || p->N >= (1ll << 31) - 512 || p->batch >= (1ll << 31)) return MCF_EUNSUPPORTED;
+    const int64_t *in[4] = {p->a_stride, p->b_stride, p->d_stride, p->e_stride};
+    int64_t *out[4] = {o->sa, o->sb, o->sd, o->se};
+    const int64_t rows[4] = {p->M, p->K, p->N, p->M}, cols[4] = {p->K, p->N, p->L, p->L};
+    for (int t = 0; t < 4; ++t) {
+        if (all_zero(in[t])) packed(out[t], rows[t], cols[t]);
+        else memcpy(out[t], in[t], 3 * sizeof(int64_t));
+        for (int d = 0; d < 3; ++d)
+            if (out[t][d] < 0) return MCF_EINVAL;
+    }
+    // contiguous index of each tensor
+    if (o->sa[2] != 1 || o->sd[2] != 1 || o->se[2] != 1) return MCF_EUNSUPPORTED;
+    // B: N contiguous (col stride 1) or K contiguous (row stride 1); N-contiguous wins a tie.
+    if (o->sb[2] == 1) o->b_kcontig = 0;
+    else if (o->sb[1] == 1) o->b_kcontig = 1;
+    else return MCF_EUNSUPPORTED;
+    // rows must not overlap themselves
+    if (p->M > 1 && o->sa[1] < p->K) return MCF_EINVAL;
+    if (p->N > 1 && o->sd[1] < p->L) return MCF_EINVAL;
+    if (p->M > 1 && o->se[1] < p->L) return MCF_EINVAL;
+    if (o->b_kcontig ? (p->N > 1 && o->sb[2] < p->K) : (p->K > 1 && o->sb[1] < p->N)) return MCF_EINVAL;
+    // 16-byte vector accesses: leading strides and batch strides in multiples of 8 elements
+    const int64_t lead[4] = {o->sa[1], o->b_kcontig ? o->sb[2] : o->sb[1], o->sd[1], o->se[1]};
+    const int64_t bstr[4] = {o->sa[0], o->sb[0], o->sd[0], o->se[0]};
+    for (int t = 0; t < 4; ++t)
+        if (lead[t] % 8 != 0 || bstr[t] % 8 != 0) return MCF_EALIGN;
+    if (!o->b_kcontig && p->N % 8 != 0) return MCF_EUNSUPPORTED;
+    return MCF_OK;
+}
+
+// Elements spanned by a [batch, rows, cols] tensor with the given strides.
+static int64_t span(int64_t batch, int64_t rows, int64_t cols, const int64_t s[3]) {
+    if (batch == 0 || rows == 0 || cols == 0) return 0;
+    return 1 + (batch - 1) * s[0] + (rows - 1) * s[1] + (cols - 1) * s[2];
+}
+
+static bool overlaps(const void *x, int64_t xe, const void *y, int64_t ye) {
+    const char *a = (const char *)x, *b = (const char *)y;
+    return xe > 0 && ye > 0 && a < b + 2 * ye && b < a + 2 * xe;
+}
+
+static int run(const mcf_problem *p, int softmax, float scale, const void *A, const void *B, const void *D, void *E,
+               const mcf_tiles *tiles, void *stream) {
+    set_last_error("");
+    if (!p) return MCF_EINVAL;
+    if (p->batch < 0 || p->M < 0 || p->K < 0 || p->N < 0 || p->L < 0) return MCF_EINVAL;
+    Layout lay;
+    int st = decode_layout(p, &lay);
+    if (st != MCF_OK) return st;
+    if (softmax && !(scale == scale && fabsf(scale) <= 3.0e38f)) return MCF_EINVAL; // NaN / inf scale
+    if (p->batch == 0 || p->M == 0 || p->L == 0) return MCF_OK;
+    if (softmax && p->N == 0) return MCF_EINVAL;
+    if (!A || !E || (p->N > 0 && (!B || !D))) return MCF_EINVAL;
+
+    const int64_t ea = span(p->batch, p->M, p->K, lay.sa), eb = span(p->batch, p->K, p->N, lay.sb);
+    const int64_t ed = span(p->batch, p->N, p->L, lay.sd), ee = span(p->batch, p->M, p->L, lay.se);
+    if (overlaps(E, ee, A, ea) || overlaps(E, ee, B, eb) || overlaps(E, ee, D, ed)) return MCF_EINVAL;
+    const uintptr_t ptrs[4] = {(uintptr_t)A, (uintptr_t)B, (uintptr_t)D, (uintptr_t)E};
+    for (int t = 0; t < 4; ++t)
+        if (ptrs[t] % 16 != 0) return MCF_EALIGN;
+
+    mcf_tiles chosen;
+    if (tiles) {
+        chosen = *tiles;
+    } else {
+        st = mcf_pick_tiles(p, softmax, &chosen);
+        if (st != MCF_OK) return st;
+    }
+    const Variant *v = find_variant(p->in_dtype, (int)p->K, (int)p->L, softmax, lay.b_kcontig, chosen.mb, chosen.rg, chosen.ns);
+    if (!v) return tiles ? MCF_EINVAL : MCF_EUNSUPPORTED;
+
+    const int64_t tm = 32ll * v->mb * v->rg;
+    const int64_t m_tiles = (p->M + tm - 1) / tm;
+    if (p->batch * m_tiles >= (1ll << 31)) return MCF_EUNSUPPORTED;
+
+    KParams k;
+    memset(&k, 0, sizeof(k));
+    k.A = A; k.B = B; k.D = D; k.E = E;
+    k.sa_b = lay.sa[0]; k.sa_r = lay.sa[1];
+    k.sb_b = lay.sb[0]; k.sb_r = lay.b_kcontig ? lay.sb[2] : lay.sb[1];
+    k.sd_b = lay.sd[0]; k.sd_r = lay.sd[1];
+    k.se_b = lay.se[0]; k.se_r = lay.se[1];
+    k.M = (int32_t)p->M; k.N = (int32_t)p->N;
+    k.m_tiles = (int32_t)m_tiles;
+    k.n_blocks = (int32_t)(p->batch * m_tiles);
+    k.c1 = 1.0f; k.a_mode = 0;
+    if (softmax) {
+        // exp(scale*s - max) = exp2(|scale|*log2(e) * (s' - max')) with s' = +-s; a zero scale
+        // makes every logit equal, which is what A := 0 gives.
+        const float log2e = 1.4426950408889634f;
+        if (scale == 0.0f) { k.a_mode = 2; k.c1 = log2e; }
+        else { k.a_mode = scale < 0.0f ? 1 : 0; k.c1 = fabsf(scale) * log2e; }
+    }
+    int err = v->launch(k, stream);
+    if (err != 0) {
+        set_last_error(hipGetErrorString((hipError_t)err));
+        return MCF_ELAUNCH;
+    }
+    return MCF_OK;
+}
+
+} // namespace mcf
+
+extern "C" int mcf_gemm_chain(const mcf_problem *p, const void *A, const void *B, const void *D, void *E,
+                              const mcf_tiles *tiles, void *stream) {
+    return mcf::run(p, 0, 1.0f, A, B, D, E, tiles, stream);
+}
+
+extern "C" int mcf_softmax_gemm_chain(const mcf_problem *p, float scale, const void *A, const void *B, const void *D,
+                                      void *E, const mcf_tiles *tiles, void *stream) {
+    return mcf::run(p, 1, scale, A, B, D, E, tiles, stream);
+}
+
+extern "C" const char *mcf_status_string(int s) {
+    switch (s) {
+    case MCF_OK: return "MCF_OK";
+    case MCF_EINVAL: return "MCF_EINVAL: invalid argument";
+    case MCF_EUNSUPPORTED: return "MCF_EUNSUPPORTED: no kernel variant covers this problem";
+    case MCF_EALIGN: return "MCF_EALIGN: pointer or stride not 16-byte aligned";
+    case MCF_ELAUNCH: return "MCF_ELAUNCH: HIP launch failed";
+    default: return "unknown mcf status";
+    }
+}
+
+extern "C" const char *mcf_last_error(void) { return mcf::g_last_error; }

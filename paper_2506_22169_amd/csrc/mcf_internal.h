@@ -1,0 +1,59 @@
+// Internal declarations shared by the host files of the library (never installed).
+#pragma once
+#include <stdint.h>
+
+#include "../../include/mcf.h"
+
+namespace mcf {
+
+// Machine constants of MI355X used by the picker (Sec. IV-A: W, P, N_SM of eq. (3)-(5)).
+constexpr double kHbmBytesPerSec = 8.0e12;    // W: HBM3E peak
+constexpr double kL2BytesPerSec = 32.0e12;    // bandwidth charged to re-reads served by L2/MALL
+constexpr double kMfmaFlopsPerSec = 2.5e15;   // P: dense fp16/bf16 MFMA peak
+constexpr int kComputeUnits = 256;            // N_SM
+constexpr int kLdsBytesPerBlock = 160 * 1024; // Shm_max of Rule 4
+constexpr int kVgprBudget = 512;              // arch + accumulation VGPRs per lane at 1 wave/SIMD
+
+// Kernel arguments (device pointers, element strides).
+struct KParams {
+    const void *A, *B, *D;
+    void *E;
+    int64_t sa_b, sa_r; // A: batch / row stride (col stride 1)
+    int64_t sb_b, sb_r; // B: batch stride / stride of the non-contiguous index
+    int64_t sd_b, sd_r; // D: batch / row stride
+    int64_t se_b, se_r; // E: batch / row stride
+    int32_t M, N;
+    int32_t m_tiles;    // ceil(M / T_M)
+    int32_t n_blocks;   // batch * m_tiles
+    float c1;           // |scale| * log2(e) (softmax only)
+    int32_t a_mode;     // 0: A as is, 1: -A (negative scale), 2: A := 0 (scale == 0)
+};
+
+typedef int (*LaunchFn)(const KParams &p, void *stream); // returns hipError_t as int
+
+struct Variant {
+    int32_t dtype, K, L;
+    int32_t mb, rg, ns;
+    int32_t softmax, b_kcontig;
+    int32_t lds_bytes;
+    LaunchFn launch;
+};
+
+// Registry of every built kernel variant (defined in mcf_registry.cpp).
+const Variant *variants(int *count);
+const Variant *find_variant(int dtype, int K, int L, int softmax, int b_kcontig, int mb, int rg, int ns);
+
+// Layout decoded from an mcf_problem.
+struct Layout {
+    int64_t sa[3], sb[3], sd[3], se[3];
+    int b_kcontig;
+};
+int decode_layout(const mcf_problem *p, Layout *out); // MCF_OK or an error status
+
+// LDS bytes a variant needs (two stages of a B tile and a D tile, padded rows).
+int lds_bytes_for(int K, int L, int mb, int rg, int ns, int b_kcontig);
+int vgpr_estimate(int K, int L, int mb, int rg, int ns, int softmax);
+
+void set_last_error(const char *msg);
+
+} // namespace mcf

@@ -1,0 +1,149 @@
+// Tile picker: the analytical model of Sec. IV-A (eq. (2)-(5)) evaluated over the kernel
+// variants built into the library, under Rule 3 (padding) and Rule 4 / eq. (1) (on-chip
+// memory) of Sec. III-C.  Pure host arithmetic; needs no GPU.
+//
+// Per-block tiling expression: n( k(L_A, L_B, C_C), L_D, C_E ), S_E with T_K = K and T_L = L.
+// k and h have extent 1, so (Sec. III-B) L_A is governed by m alone and S_E by m, h:
+//     trips(L_A) = trips(S_E) = batch * m          m = ceil(M / T_M)
+//     trips(L_B) = trips(L_D) = batch * m * n      n = ceil(N / T_N)
+//     trips(C_C) = trips(C_E) = batch * m * n
+// Differences from the printed model, each a reading made for this machine:
+//   * eq. (3) charges every byte at one bandwidth W.  Here the first touch of each tensor (the
+//     compulsory bytes) is charged at HBM bandwidth and the re-reads of B and D by the other
+//     m-tiles of a batch at the L2 bandwidth, because on MI355X they are served by the XCD's
+//     L2 / the memory-side cache, not by HBM.
+//   * eq. (1) sums all five tiles against shared memory.  Here C and E (and A) live in
+//     registers, so the sum is split: B and D tiles (two stages, padded rows) against the
+//     160 KiB LDS, and A, C, E tiles against the 512-VGPR budget of a lane.  Both estimates
+//     are exact for hand-written kernels, so the 1.2x slack of Rule 4 is not applied.
+//   * N_SM of eq. (5) is the number of compute units (256).
+#include <math.h>
+#include <string.h>
+
+#include "mcf_geometry.h"
+#include "mcf_internal.h"
+
+namespace mcf {
+
+int lds_bytes_for(int K, int L, int mb, int rg, int ns, int b_kcontig) {
+    return total_lds_bytes(K, L, mb, rg, ns, b_kcontig != 0);
+}
+
+// Registers per lane: A tile (mb*K/16 operands of 4 VGPRs), E accumulators (mb * L/32 * 16),
+// one C accumulator and its 16-bit copy per mb, the staged global->LDS chunks, and a fixed
+// allowance for addresses and softmax state.
+int vgpr_estimate(int K, int L, int mb, int rg, int ns, int softmax) {
+    const int nt = 64 * rg * ns, tn = 32 * ns;
+    const int staged = ((K * tn / 8 + nt - 1) / nt + (tn * L / 8 + nt - 1) / nt) * 4;
+    return mb * (K / 16) * 4 + mb * (L / 32) * 16 + mb * (16 + 8) + staged + 40 + (softmax ? 24 : 0);
+}
+
+static bool is_pow2(int64_t x) { return x > 0 && (x & (x - 1)) == 0; }
+
+// Rule 3: a power-of-two dimension takes no padding; otherwise the padding ratio stays < 0.05.
+static bool padding_ok(int64_t dim, int64_t tile) {
+    const int64_t padded = (dim + tile - 1) / tile * tile;
+    if (is_pow2(dim)) return padded == dim;
+    return (double)(padded - dim) < 0.05 * (double)dim;
+}
+
+static void eval_model(const mcf_problem *p, int softmax, int b_kcontig, int mb, int rg, int ns, mcf_tiles *t) {
+    memset(t, 0, sizeof(*t));
+    t->mb = mb; t->rg = rg; t->ns = ns;
+    t->tm = 32 * mb * rg; t->tn = 32 * ns; t->tk = (int32_t)p->K; t->tl = (int32_t)p->L;
+    t->waves = rg * ns;
+    t->lds_bytes = lds_bytes_for((int)p->K, (int)p->L, mb, rg, ns, b_kcontig);
+    t->vgpr_est = vgpr_estimate((int)p->K, (int)p->L, mb, rg, ns, softmax);
+    const int64_t es = 2; // bytes per element, fp16 / bf16
+    const int64_t m = (p->M + t->tm - 1) / t->tm, n = (p->N + t->tn - 1) / t->tn;
+    t->blocks = p->batch * m;
+    t->compulsory_bytes = es * p->batch * (p->M * p->K + p->K * p->N + p->N * p->L + p->M * p->L);
+    const int64_t la = (int64_t)t->tm * p->K * es * p->batch * m;
+    const int64_t lb = (int64_t)p->K * t->tn * es * p->batch * m * n;
+    const int64_t ld = (int64_t)t->tn * p->L * es * p->batch * m * n;
+    const int64_t se = (int64_t)t->tm * p->L * es * p->batch * m;
+    t->model_bytes = la + lb + ld + se;
+    t->flops = (2 * (int64_t)t->tm * t->tn * p->K + 2 * (int64_t)t->tm * t->tn * p->L) * p->batch * m * n;
+    const int64_t reread = t->model_bytes > t->compulsory_bytes ? t->model_bytes - t->compulsory_bytes : 0;
+    t->t_mem_s = (double)t->compulsory_bytes / kHbmBytesPerSec + (double)reread / kL2BytesPerSec;
+    t->t_comp_s = (double)t->flops / kMfmaFlopsPerSec;
+    t->alpha = t->blocks > 0 ? (double)(t->blocks + kComputeUnits) / (double)t->blocks : 1.0;
+    t->t_est_s = (t->t_mem_s + t->t_comp_s) * t->alpha;
+}
+
+static bool feasible(const mcf_tiles &t) { return t.lds_bytes <= kLdsBytesPerBlock && t.vgpr_est <= kVgprBudget; }
+
+// Strict ordering of candidates: smaller estimate first; among equal estimates (the model
+// does not see how the waves of a block are arranged) more waves per block, then fewer
+// waves across n (less to combine), then fewer rows per wave.
+static bool better(const mcf_tiles &a, const mcf_tiles &b) {
+    if (a.t_est_s != b.t_est_s) return a.t_est_s < b.t_est_s;
+    if (a.waves != b.waves) return a.waves > b.waves;
+    if (a.ns != b.ns) return a.ns < b.ns;
+    return a.mb < b.mb;
+}
+
+static int check_problem(const mcf_problem *p, Layout *lay) {
+    if (!p) return MCF_EINVAL;
+    if (p->batch < 0 || p->M < 0 || p->K < 0 || p->N < 0 || p->L < 0) return MCF_EINVAL;
+    return decode_layout(p, lay);
+}
+
+} // namespace mcf
+
+using namespace mcf;
+
+extern "C" int mcf_list_variants(const mcf_problem *p, int softmax, int32_t *out, int cap) {
+    Layout lay;
+    if (check_problem(p, &lay) != MCF_OK) return 0;
+    int n = 0, total = 0;
+    const Variant *v = variants(&n);
+    for (int i = 0; i < n; ++i) {
+        if (v[i].dtype != p->in_dtype || v[i].K != p->K || v[i].L != p->L || v[i].softmax != (softmax != 0) ||
+            v[i].b_kcontig != lay.b_kcontig)
+            continue;
+        if (out && total < cap) {
+            out[3 * total] = v[i].mb; out[3 * total + 1] = v[i].rg; out[3 * total + 2] = v[i].ns;
+        }
+        ++total;
+    }
+    return total;
+}
+
+extern "C" int mcf_eval_tiles(const mcf_problem *p, int softmax, mcf_tiles *t) {
+    Layout lay;
+    if (!t) return MCF_EINVAL;
+    int st = check_problem(p, &lay);
+    if (st != MCF_OK) return st;
+    const int mb = t->mb, rg = t->rg, ns = t->ns;
+    if (!find_variant(p->in_dtype, (int)p->K, (int)p->L, softmax != 0, lay.b_kcontig, mb, rg, ns)) return MCF_EUNSUPPORTED;
+    eval_model(p, softmax != 0, lay.b_kcontig, mb, rg, ns, t);
+    return feasible(*t) ? MCF_OK : MCF_EINVAL;
+}
+
+extern "C" int mcf_pick_tiles(const mcf_problem *p, int softmax, mcf_tiles *out) {
+    Layout lay;
+    if (!out) return MCF_EINVAL;
+    int st = check_problem(p, &lay);
+    if (st != MCF_OK) return st;
+    int n = 0;
+    const Variant *v = variants(&n);
+    // Two passes: with Rule 3, and without it if Rule 3 leaves nothing (e.g. M smaller than
+    // every tile), so that a feasible variant is always found when one covers the shape.
+    for (int pass = 0; pass < 2; ++pass) {
+        bool have = false;
+        mcf_tiles best;
+        for (int i = 0; i < n; ++i) {
+            if (v[i].dtype != p->in_dtype || v[i].K != p->K || v[i].L != p->L || v[i].softmax != (softmax != 0) ||
+                v[i].b_kcontig != lay.b_kcontig)
+                continue;
+            mcf_tiles t;
+            eval_model(p, softmax != 0, lay.b_kcontig, v[i].mb, v[i].rg, v[i].ns, &t);
+            if (!feasible(t)) continue;
+            if (pass == 0 && p->M > 0 && p->N > 0 && !(padding_ok(p->M, t.tm) && padding_ok(p->N, t.tn))) continue;
+            if (!have || better(t, best)) { best = t; have = true; }
+        }
+        if (have) { *out = best; return MCF_OK; }
+    }
+    return MCF_EUNSUPPORTED;
+}

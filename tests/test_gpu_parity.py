@@ -1,0 +1,155 @@
+"""Parity of the HIP path (through the C ABI) with the fp64 oracle, element by element, on
+seeded inputs that span several tiles and ragged tails.  Needs an MI355X."""
+import numpy as np
+import pytest
+import torch
+
+import mcf_inputs as mi
+import oracle
+import paper_2506_22169_amd as mcf
+from paper_2506_22169_amd.binding import make_problem as c_problem
+
+from gpu_util import TOL, check_full, device_inputs, run_gpu, to_device, to_host64
+
+pytestmark = pytest.mark.gpu
+
+WAVE_SHAPES = [(1, 4, 1), (1, 2, 2), (1, 1, 4), (2, 4, 1), (2, 2, 2), (1, 2, 1), (1, 1, 2), (1, 4, 2)]
+
+
+@pytest.mark.parametrize("softmax", [False, True])
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("KL", [32, 64, 128])
+def test_every_variant_small_ragged(KL, dtype, softmax):
+    """Every built wave arrangement on a shape with a ragged m tail and a ragged n tail that
+    spans several tiles of the largest variant (tm up to 256, tn up to 128)."""
+    # plain chains keep B as [b,K,N] (N a multiple of 8), softmax chains as the key matrix [b,N,K]
+    M, N = 600, (328 if not softmax else 333)
+    dist = "normal" if softmax else "uniform"
+    w = mi.make_problem(3, M, KL, N, KL, dtype, softmax, dist, seed=1000 + KL)
+    worst = 0.0
+    for tiles in WAVE_SHAPES:
+        print(f"case KL={KL} {dtype} softmax={softmax} tiles={tiles}", flush=True)
+        worst = max(worst, check_full(w, tiles))
+    print(f"worst max|err|/max|oracle| = {worst:.3e}", flush=True)
+
+
+@pytest.mark.parametrize("layout", ["kn", "nk"])
+@pytest.mark.parametrize("softmax", [False, True])
+def test_both_b_layouts(softmax, layout):
+    """Plain chain with a K-contiguous B and softmax chain with an N-contiguous B (the
+    combinations the workloads themselves do not use)."""
+    w = mi.make_problem(2, 256, 64, 256, 64, "f16", softmax, "normal" if softmax else "uniform", seed=77)
+    x = mi.make_inputs(w)
+    A, B, D = device_inputs(w, x)
+    if (x["b_layout"] == "nk") != (layout == "nk"):
+        B = B.transpose(1, 2).contiguous().transpose(1, 2) if layout == "nk" else B.contiguous()
+    assert (B.stride(1) == 1) == (layout == "nk")
+    E = mcf.softmax_gemm_chain(A, B, D, w.scale) if softmax else mcf.gemm_chain(A, B, D)
+    torch.cuda.synchronize()
+    ref = oracle.chain(x["A"], x["B"], x["D"], softmax=softmax, scale=w.scale)
+    assert np.max(np.abs(to_host64(E, "f16") - ref)) <= TOL * np.max(np.abs(ref))
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4"])
+def test_workload_full_size(name):
+    """The evaluation workloads at full size with the picker's tiles, every element."""
+    w = mi.WORKLOADS[name]
+    print(f"case {name}", flush=True)
+    r = check_full(w)
+    print(f"{name}: max|err|/max|oracle| = {r:.3e}", flush=True)
+
+
+def test_cfg5_sampled_rows():
+    """Long-sequence softmax chain at full size: the whole output is produced by the launch
+    bench.py would time; 4 heads are compared in 256 sampled rows each plus 64 rows sampled
+    over all heads (the oracle needs ~2 MFLOP per row in fp64)."""
+    w = mi.WORKLOADS["cfg5"]
+    x = mi.make_inputs(w, values=False)
+    A, B, D = device_inputs(w, x)
+    E = mcf.softmax_gemm_chain(A, B, D, w.scale)
+    torch.cuda.synchronize()
+    assert torch.isfinite(E.float()).all()
+    rng = np.random.default_rng(5)
+    rows = [(b, i) for b in (0, 21, 42, 63) for i in rng.choice(w.M, 256, replace=False)]
+    rows += [(int(b), int(i)) for b, i in zip(rng.integers(0, w.batch, 64), rng.integers(0, w.M, 64))]
+    rows = np.array(rows, dtype=np.int64)
+    heads = sorted(set(rows[:, 0].tolist()))
+    remap = {h: j for j, h in enumerate(heads)}
+    sel = np.array(heads)
+    A64 = mi.from_bits(x["a_bits"][sel], w.dtype)
+    B64 = mi.from_bits(x["b_bits"][sel], w.dtype).transpose(0, 2, 1)
+    D64 = mi.from_bits(x["d_bits"][sel], w.dtype)
+    local = np.array([[remap[b], i] for b, i in rows], dtype=np.int64)
+    ref = oracle.chain_rows(A64, B64, D64, local, softmax=True, scale=w.scale)
+    got = to_host64(E[torch.from_numpy(rows[:, 0]).cuda(), torch.from_numpy(rows[:, 1]).cuda()], w.dtype)
+    scale = np.max(np.abs(ref))
+    err = np.max(np.abs(got - ref))
+    print(f"cfg5: max|err|/max|oracle| = {err / scale:.3e} over {len(rows)} rows", flush=True)
+    assert err <= TOL * scale
+    # property that holds at any size: each output is a convex combination of rows of V
+    Dmax = torch.amax(D.float(), dim=1, keepdim=True)
+    Dmin = torch.amin(D.float(), dim=1, keepdim=True)
+    assert bool(((E.float() <= Dmax + 1e-2) & (E.float() >= Dmin - 1e-2)).all())
+
+
+def test_edge_cases():
+    dev = "cuda"
+    # empty batch / M: no-op, N == 0: zeros (plain) or error (softmax)
+    for shape in [(0, 64, 64, 64, 64), (2, 0, 64, 64, 64)]:
+        b, M, K, N, L = shape
+        A = torch.zeros((b, M, K), dtype=torch.float16, device=dev)
+        B = torch.zeros((b, K, N), dtype=torch.float16, device=dev)
+        D = torch.zeros((b, N, L), dtype=torch.float16, device=dev)
+        assert tuple(mcf.gemm_chain(A, B, D).shape) == (b, M, L)
+    A = torch.ones((2, 40, 64), dtype=torch.float16, device=dev)
+    B = torch.zeros((2, 64, 0), dtype=torch.float16, device=dev)
+    D = torch.zeros((2, 0, 64), dtype=torch.float16, device=dev)
+    E = torch.full((2, 40, 64), 7.0, dtype=torch.float16, device=dev)
+    mcf.gemm_chain(A, B, D, out=E)
+    torch.cuda.synchronize()
+    assert not E.any()
+    with pytest.raises(mcf.McfError):
+        mcf.softmax_gemm_chain(A, B, D, 1.0)
+    # one row, one column (softmax over a single logit is 1 -> E = V)
+    w = mi.make_problem(2, 1, 64, 1, 64, "bf16", True, "normal", seed=3)
+    assert check_full(w) < TOL
+    # negative and zero softmax scale
+    w = mi.make_problem(2, 96, 32, 80, 32, "f16", True, "normal", seed=4)
+    x = mi.make_inputs(w)
+    A, B, D = device_inputs(w, x)
+    for scale in (-0.3, 0.0):
+        E = mcf.softmax_gemm_chain(A, B, D, scale)
+        torch.cuda.synchronize()
+        ref = oracle.chain(x["A"], x["B"], x["D"], softmax=True, scale=scale)
+        assert np.max(np.abs(to_host64(E, "f16") - ref)) <= TOL * np.max(np.abs(ref))
+    # strided (non-packed) operands and output
+    w = mi.make_problem(2, 70, 64, 72, 64, "f16", False, "uniform", seed=5)
+    x = mi.make_inputs(w)
+    A, B, D = device_inputs(w, x)
+    Abig = torch.zeros((2, 70, 128), dtype=torch.float16, device=dev); Abig[:, :, :64] = A
+    Ebig = torch.zeros((2, 80, 64), dtype=torch.float16, device=dev)
+    mcf.gemm_chain(Abig[:, :, :64], B, D, out=Ebig[:, :70, :])
+    torch.cuda.synchronize()
+    ref = oracle.chain(x["A"], x["B"], x["D"])
+    assert np.max(np.abs(to_host64(Ebig[:, :70, :], "f16") - ref)) <= TOL * np.max(np.abs(ref))
+    assert not Ebig[:, 70:, :].any()
+
+
+def test_error_codes_from_the_abi():
+    dev = "cuda"
+    A = torch.zeros((1, 64, 64), dtype=torch.float16, device=dev)
+    B = torch.zeros((1, 64, 64), dtype=torch.float16, device=dev)
+    D = torch.zeros((1, 64, 64), dtype=torch.float16, device=dev)
+    with pytest.raises(mcf.McfError) as e:          # K = 48 has no variant
+        mcf.gemm_chain(A[:, :, :48], B[:, :48, :], D)
+    assert e.value.status == 2
+    with pytest.raises(mcf.McfError) as e:          # misaligned base pointer
+        flat = torch.zeros(64 * 64 + 8, dtype=torch.float16, device=dev)
+        mcf.gemm_chain(flat[1:1 + 4096].view(1, 64, 64), B, D)
+    assert e.value.status == 3
+    with pytest.raises(mcf.McfError) as e:          # output aliases an input
+        mcf.gemm_chain(A, B, D, out=A)
+    assert e.value.status == 1
+    with pytest.raises(mcf.McfError) as e:          # no such wave arrangement
+        mcf.gemm_chain(A, B, D, tiles=(3, 1, 1))
+    assert e.value.status == 1
