@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused MBCI chain on one MI355X.
+
+A step is one pass of the whole hot path (tile pick on the host, then the fused kernel:
+A tile -> registers, B/D tiles -> LDS, GEMM 1, [softmax], GEMM 2, store E) over one batch of
+synthetic input.  Inputs are resident in HBM before the timed region starts.  Because the
+small workloads fit in the 256 MB memory-side cache, steps rotate over enough distinct
+input/output sets (> 768 MiB in total) that every step's operands come from HBM.
+
+The K timed steps are captured once into a HIP graph (each step is still one call of the
+C ABI on the capturing stream) and replayed, so the figure is device throughput and not the
+Python call overhead; --eager times plain calls instead.
+
+Prints ONE JSON line: the BASELINE metric (effective HBM GB/s on compulsory bytes) with a
+`roofline` object for the chain kernel and a `cpu_baseline` object (the fp64 oracle timed on
+this host's cores).
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
+MFMA_PEAK_TFLOPS = 2500.0  # dense fp16 / bf16
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--workload", default="cfg2", help="cfg1..cfg5 (default: cfg2, the configuration the metric is quoted on)")
+    ap.add_argument("--tiles", default=None, help="mb,rg,ns to override the picker")
+    ap.add_argument("--eager", action="store_true", help="time plain calls instead of a HIP graph replay")
+    ap.add_argument("--warm", action="store_true", help="reuse one buffer set (cache-resident operands)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic", default=None, help="JSON file with measured HBM bytes per launch (from the rocprofv3 --pmc runs)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the fused chain shards over batch / row "
+              "blocks with no exchange; no multi-GPU path is built). Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import mcf_inputs as mi
+    import paper_2506_22169_amd as mcf
+    from paper_2506_22169_amd.binding import make_problem as c_problem
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    mcf.load_library()  # fail loudly if the HIP library is not built
+
+    w = mi.WORKLOADS[args.workload]
+    tdt = torch.float16 if w.dtype == "f16" else torch.bfloat16
+    tiles = tuple(int(v) for v in args.tiles.split(",")) if args.tiles else None
+
+    # ---- inputs: set 0 is the seeded workload; the other sets are batch-rotations of it ----
+    x = mi.make_inputs(w, values=False)
+
+    def dev(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(tdt).cuda()
+
+    A0, B0s, D0 = dev(x["a_bits"]), dev(x["b_bits"]), dev(x["d_bits"])
+    per_set = w.compulsory_bytes
+    n_sets = 1 if args.warm else max(2, min(64, math.ceil(768 * 2**20 / per_set)))
+    if per_set * n_sets > 8 * 2**30:
+        n_sets = max(2, (8 * 2**30) // per_set)
+    sets = []
+    for s in range(n_sets):
+        sh = s % max(w.batch, 1)
+        A = A0 if s == 0 else torch.roll(A0, sh, 0).contiguous()
+        Bs = B0s if s == 0 else torch.roll(B0s, sh, 0).contiguous()
+        D = D0 if s == 0 else torch.roll(D0, sh, 0).contiguous()
+        B = Bs.transpose(1, 2) if w.softmax else Bs
+        E = torch.empty((w.batch, w.M, w.L), dtype=tdt, device="cuda")
+        sets.append((A, B, D, E))
+
+    def step(i):
+        A, B, D, E = sets[i % n_sets]
+        if w.softmax:
+            mcf.softmax_gemm_chain(A, B, D, w.scale, out=E, tiles=tiles)
+        else:
+            mcf.gemm_chain(A, B, D, out=E, tiles=tiles)
+
+    prob = c_problem(w.batch, w.M, w.K, w.N, w.L, w.dtype,
+                     b_stride=(w.N * w.K, 1, w.K) if w.softmax else None)
+    picked = mcf.pick_tiles(prob, w.softmax) if tiles is None else mcf.eval_tiles(prob, *tiles, softmax=w.softmax)
+
+    # ---- warm-up (also sets kernel attributes before any capture) -------------------------
+    for i in range(max(args.warmup, 1)):
+        step(i)
+    torch.cuda.synchronize()
+
+    graph = None
+    if not args.eager:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):      # the binding launches on torch's current (capturing) stream
+            for i in range(args.steps):
+                step(i)
+        graph.replay()  # one untimed replay
+        torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps ------------------------------------------------------
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()
+    if graph is not None:
+        graph.replay()
+    else:
+        for i in range(args.steps):
+            step(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_s = time.perf_counter() - t0
+    dev_s = ev0.elapsed_time(ev1) * 1e-3
+    t_step = wall_s / args.steps          # whole-job figure: host clock around the region
+    t_kernel = dev_s / args.steps         # HIP events on the launch stream: average per launch
+
+    gbs = per_set / t_step / 1e9
+    tflops = w.flops / t_step / 1e12
+    ai = w.flops / per_set
+    bound = "hbm" if ai < MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9) else "mfma"
+    if bound == "hbm":
+        achieved, peak, unit = per_set / t_kernel / 1e9, HBM_PEAK_GBS, "GB/s"
+    else:
+        achieved, peak, unit = w.flops / t_kernel / 1e12, MFMA_PEAK_TFLOPS, "TFLOP/s"
+    traffic = None
+    if args.traffic and os.path.exists(args.traffic):
+        traffic = json.load(open(args.traffic)).get(args.workload)
+
+    # ---- parity of set 0 at the benchmarked configuration + oracle timing ------------------
+    cpu_baseline, parity = None, None
+    if not args.no_cpu_baseline:
+        import oracle
+        A, B, D, E = sets[0]
+        step(0)
+        torch.cuda.synchronize()
+        full_flops = w.flops
+        nb = w.batch if full_flops <= 2.0e10 else max(1, int(w.batch * 2.0e10 / full_flops))
+        rows = None
+        A64 = mi.from_bits(x["a_bits"][:nb], w.dtype)
+        B64 = mi.from_bits(x["b_bits"][:nb], w.dtype)
+        B64 = B64.transpose(0, 2, 1) if w.softmax else B64
+        D64 = mi.from_bits(x["d_bits"][:nb], w.dtype)
+        if full_flops > 2.0e10:   # long-sequence workload: a bounded sample of rows of one head
+            rng = np.random.default_rng(0)
+            n_rows = max(64, int(2.0e10 / (2.0 * w.N * (w.K + w.L))))
+            rows = np.stack([np.zeros(n_rows, dtype=np.int64), rng.integers(0, w.M, n_rows)], axis=1)
+        tc = time.perf_counter()
+        if rows is None:
+            ref, threads = oracle.chain(A64, B64, D64, softmax=w.softmax, scale=w.scale, return_threads=True)
+            got = mi.from_bits(E[:nb].contiguous().view(torch.int16).cpu().numpy().view(np.uint16), w.dtype)
+            frac = nb / w.batch
+            sample = f"all rows of {nb} of {w.batch} batches"
+        else:
+            ref = oracle.chain_rows(A64, B64, D64, rows, softmax=w.softmax, scale=w.scale)
+            threads = os.cpu_count()
+            got = mi.from_bits(E[0][torch.from_numpy(rows[:, 1]).cuda()].contiguous().view(torch.int16)
+                               .cpu().numpy().view(np.uint16), w.dtype)
+            frac = len(rows) / (w.batch * w.M)
+            sample = f"{len(rows)} sampled rows of batch 0"
+        cpu_s = time.perf_counter() - tc
+        cpu_baseline = {"value": per_set * frac / cpu_s / 1e9, "unit": "GB/s", "cores": int(threads),
+                        "kind": "oracle", "sample": sample, "seconds": cpu_s,
+                        "gflops_fp64": w.flops * frac / cpu_s / 1e9}
+        parity = {"max_abs_err": float(np.max(np.abs(got - ref))), "max_abs_ref": float(np.max(np.abs(ref))),
+                  "tolerance": 1e-2, "checked": sample}
+        parity["ok"] = bool(parity["max_abs_err"] <= 1e-2 * parity["max_abs_ref"])
+
+    out = {
+        "metric": "fused-chain effective HBM GB/s (% of peak) and TFLOP/s per config",
+        "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": t_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: batch={w.batch} M={w.M} K={w.K} N={w.N} L={w.L} {w.dtype}"
+                               f"{' softmax' if w.softmax else ''}",
+                   "tiles": {"mb": picked.mb, "rg": picked.rg, "ns": picked.ns, "tm": picked.tm, "tn": picked.tn},
+                   "buffer_sets": n_sets, "launch": "eager" if args.eager else "hip_graph"},
+        "pct_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS, "tflops": tflops,
+        "pct_mfma_peak": 100.0 * tflops / MFMA_PEAK_TFLOPS,
+        "us_per_launch_events": t_kernel * 1e6,
+        "model_t_est_us": picked.t_est_s * 1e6,
+        "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
+                     "frac": achieved / peak, "traffic": traffic},
+        "cpu_baseline": cpu_baseline,
+        "parity": parity,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -125,9 +125,10 @@ def _problem_from_tensors(A, B, D, E):
         s = list(t.stride())
         shape = list(t.shape)
         if shape[2] <= 1:
-            s[2] = 1
+            # a single column: keep a row-contiguous (transposed) view recognisable as such
+            s[2] = shape[1] if (s[1] == 1 and shape[1] > 1) else 1
         if shape[1] <= 1:
-            s[1] = max(shape[2], 1) * s[2] if s[2] == 1 else 1
+            s[1] = max(shape[2], 1) if s[2] == 1 else 1
         if shape[0] <= 1:
             s[0] = 0
         return s

@@ -33,8 +33,9 @@ int decode_layout(const mcf_problem *p, Layout *o) {
     }
     // contiguous index of each tensor
     if (o->sa[2] != 1 || o->sd[2] != 1 || o->se[2] != 1) return MCF_EUNSUPPORTED;
-    // B: N contiguous (col stride 1) or K contiguous (row stride 1); N-contiguous wins a tie.
-    if (o->sb[2] == 1) o->b_kcontig = 0;
+    // B: N contiguous (col stride 1) or K contiguous (row stride 1); N-contiguous wins a tie
+    // unless only the K-contiguous kernels can take this N.
+    if (o->sb[2] == 1 && !(o->sb[1] == 1 && p->N % 8 != 0)) o->b_kcontig = 0;
     else if (o->sb[1] == 1) o->b_kcontig = 1;
     else return MCF_EUNSUPPORTED;
     // rows must not overlap themselves
