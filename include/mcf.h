@@ -61,7 +61,7 @@ typedef struct mcf_problem {
  * A tile choice and the model terms it was ranked by.  Tiling expression per block is the
  * paper's "nk" sub-expression with T_K = K and T_L = L (so the k and h loops have extent 1
  * and L_A / S_E are hoisted out of the n loop, Sec. III-B):
- *     block <-> (batch, m-tile);   for n-tile: { L_B, L_D -> LDS; C_C; [softmax]; C_E };  S_E
+ *     block <-> (batch, m-tile);   L_A;  for n-tile: { L_B, L_D -> LDS; C_C; [softmax]; C_E };  S_E
  * tm = 32 * mb * rg rows per block (rg wave row-groups, each wave owning 32*mb rows),
  * tn = 32 * ns columns per n-iteration (ns waves side by side in n), waves = rg * ns.
  */
@@ -69,7 +69,8 @@ typedef struct mcf_tiles {
     int32_t tm, tn, tk, tl;   /* tile sizes T_M, T_N, T_K (= K), T_L (= L)                       */
     int32_t mb, rg, ns;       /* 32-row blocks per wave, wave row-groups, waves across n         */
     int32_t waves;            /* rg * ns, 64 lanes each                                          */
-    int32_t lds_bytes;        /* eq. (1) restricted to the tiles held in LDS (B, D; 2 stages)    */
+    int32_t stages;           /* depth of the LDS ring of (B tile + D tile) buffers, 2..4        */
+    int32_t lds_bytes;        /* eq. (1) restricted to the tiles held in LDS (B, D; x stages)    */
     int32_t vgpr_est;         /* eq. (1) restricted to the tiles held in registers (A, C, E)     */
     int64_t blocks;           /* N_block of eq. (5)                                              */
     int64_t compulsory_bytes; /* A, B, D read once + E written once                              */

@@ -33,7 +33,7 @@ class Tiles(ctypes.Structure):
     """struct mcf_tiles"""
     _fields_ = [("tm", ctypes.c_int32), ("tn", ctypes.c_int32), ("tk", ctypes.c_int32), ("tl", ctypes.c_int32),
                 ("mb", ctypes.c_int32), ("rg", ctypes.c_int32), ("ns", ctypes.c_int32),
-                ("waves", ctypes.c_int32), ("lds_bytes", ctypes.c_int32), ("vgpr_est", ctypes.c_int32),
+                ("waves", ctypes.c_int32), ("stages", ctypes.c_int32), ("lds_bytes", ctypes.c_int32), ("vgpr_est", ctypes.c_int32),
                 ("blocks", ctypes.c_int64), ("compulsory_bytes", ctypes.c_int64),
                 ("model_bytes", ctypes.c_int64), ("flops", ctypes.c_int64),
                 ("t_mem_s", ctypes.c_double), ("t_comp_s", ctypes.c_double),

@@ -15,7 +15,7 @@ OBJ_DIR = os.path.join(ROOT, "_build", "mcf")
 LIB = os.path.join(HERE, "libmcf.so")
 
 # -packed-fp32-ops is switched off on purpose: hipcc must not form packed fp32 instructions.
-HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 

@@ -2,11 +2,11 @@
 //
 // Per-block schedule = the paper's "nk" sub-tiling expression with T_K = K, T_L = L
 // (Sec. III-B/C): the k and h loops have extent 1, so L_A is hoisted to the block (A tile
-// loaded once into registers) and S_E is hoisted out of the n loop (E stored once):
+// loaded once) and S_E is hoisted out of the n loop (E stored once):
 //
 //   block <-> (batch, m-tile)                               [spatial loops on the block index]
-//   A tile -> VGPRs                                         [L_A, once]
-//   for each n-tile:   B tile, D tile -> LDS (2 stages)     [L_B, L_D]
+//   A tile -> LDS -> VGPRs                                  [L_A, once]
+//   for each n-tile:   B tile, D tile -> LDS ring           [L_B, L_D]
 //                      C^T = B^T . A^T        (MFMA)        [C_C]
 //                      optional online softmax on C^T, convert to 16-bit in registers
 //                      E^T += D^T . C^T       (MFMA)        [C_E]
@@ -14,6 +14,13 @@
 //
 // Both GEMMs are computed transposed so that the fp32 accumulator of the first is, lane for
 // lane, already the second operand of the second: the intermediate never leaves registers.
+//
+// Global -> LDS traffic uses the direct-to-LDS load (global_load_lds_dwordx4: every lane
+// names a 16-byte global source, the wave's 64 pieces land contiguously in LDS), issued
+// several n-tiles ahead into a ring of `stages` buffers and retired with counted
+// s_waitcnt vmcnt, so no registers are spent on staging and the prefetch depth covers the
+// HBM latency.  LDS tiles keep their natural row pitch; bank conflicts are avoided by an XOR
+// swizzle of the 16-byte chunk index applied on the global-source side of the load.
 //
 // MFMA v_mfma_f32_32x32x16_{f16,bf16}: lane l = (c = l%32, g = l/32).
 //   first operand  X[32 x 16]: lane holds X[c][8g .. 8g+7]
@@ -38,7 +45,10 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short i16x4 __attribute__((ext_vector_type(4)));
 typedef short i16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) unsigned char lds_u8;
 typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
+typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+typedef __attribute__((address_space(3))) float lds_f32;
 
 template <typename T> struct Mfma;
 template <> struct Mfma<_Float16> {
@@ -68,33 +78,69 @@ static __device__ __forceinline__ float xhalf_sum(float x) {
 
 // Transposing LDS read: within each group of 16 lanes, lane i points at 4 consecutive 16-bit
 // elements; lane j receives element (j%4) of the pieces addressed by lanes 4e + j/4, e = 0..3.
-static __device__ __forceinline__ i16x4 lds_read_tr(const unsigned char *p) {
+static __device__ __forceinline__ i16x4 lds_read_tr(const lds_u8 *p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4 *)p);
+}
+
+// Direct global -> LDS load of 16 bytes per lane: lane i's piece lands at lds_addr + 16*i.
+// lds_addr (a byte address in LDS) and base are wave-uniform; voff is the lane's byte offset
+// from base.  Written as inline assembly so that the compiler does not serialise later LDS
+// reads behind every outstanding load; completion is awaited with wait_vm<>().
+static __device__ __forceinline__ void dma16(unsigned lds_addr, unsigned voff, const void *base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(base)
+                 : "memory", "m0");
+}
+template <int N> static __device__ __forceinline__ void wait_vm() {
+    static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// Marks a wave-uniform value as such for the register allocator (it must live in SGPRs to
+// feed M0 / the scalar base of a direct-to-LDS load).
+static __device__ __forceinline__ unsigned uniform(unsigned v) { return __builtin_amdgcn_readfirstlane(v); }
+static __device__ __forceinline__ const void *uniform(const void *q) {
+    const uint64_t b = (uint64_t)q;
+    return (const void *)(((uint64_t)uniform((unsigned)(b >> 32)) << 32) | uniform((unsigned)b));
 }
 
 template <typename T, int KD, int LD, int MB, int RG, int NS, bool SOFTMAX, bool BKC>
 __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     using M_ = Mfma<T>;
     using v8 = typename M_::v8;
-    constexpr int NT = 64 * RG * NS;    // threads per block
-    constexpr int TM = 32 * MB * RG;    // rows per block
-    constexpr int TN = 32 * NS;         // columns per n-iteration
-    constexpr int KS = KD / 16;         // MFMA k-steps of GEMM 1
-    constexpr int HB = LD / 32;         // 32-wide h blocks of GEMM 2
-    constexpr int PB = BKC ? pitch_bk(KD) : pitch_tr(TN); // B tile row pitch (bytes)
-    constexpr int PD = pitch_tr(LD);                      // D tile row pitch (bytes)
-    constexpr int B_BYTES = b_tile_bytes(KD, TN, BKC);
-    constexpr int STAGE = stage_bytes(KD, LD, TN, BKC);
-    // 16-byte chunks of one B / D tile and how many each thread moves
-    constexpr int B_CHUNKS = KD * TN / 8;
-    constexpr int D_CHUNKS = TN * LD / 8;
-    constexpr int B_PER_T = (B_CHUNKS + NT - 1) / NT;
-    constexpr int D_PER_T = (D_CHUNKS + NT - 1) / NT;
+    constexpr int W = RG * NS;           // waves per block
+    constexpr int TM = 32 * MB * RG;     // rows per block
+    constexpr int TN = 32 * NS;          // columns per n-iteration
+    constexpr int KS = KD / 16;          // MFMA k-steps of GEMM 1
+    constexpr int HB = LD / 32;          // 32-wide h blocks of GEMM 2
+    constexpr int S = ring_stages(KD, LD, MB, RG, NS); // depth of the LDS ring
+    constexpr int RBA = 2 * KD;                  // row bytes of the A tile (rows m)
+    constexpr int RBB = BKC ? 2 * KD : 2 * TN;   // row bytes of the B tile (rows n / rows k)
+    constexpr int RBD = 2 * LD;                  // row bytes of the D tile (rows n)
+    constexpr int RBE = 2 * LD;                  // row bytes of the E staging tile (rows m)
+    constexpr int B_BYTES = b_tile_bytes(KD, TN);
+    constexpr int STAGE = stage_bytes(KD, LD, TN);
+    constexpr int A_LDS = (S - 1) * STAGE;       // the A tile borrows the last ring slot
+    // 1 KiB wave-loads per tile and per wave
+    constexpr int CA = a_tile_bytes(KD, MB, RG) / 1024;
+    constexpr int CB = B_BYTES / 1024, CT = STAGE / 1024;
+    constexpr int PA = (CA + W - 1) / W;
+    constexpr int P = (CT + W - 1) / W;
+    static_assert((S - 1) * P <= 63, "too many loads in flight for the 6-bit vmcnt counter");
 
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_generic[];
+    lds_u8 *smem = (lds_u8 *)smem_generic;
+    const unsigned lds0 = (unsigned)(size_t)smem;
+
+    // kernel arguments -> scalar registers, once
+    const int M = p.M, N = p.N, m_tiles = p.m_tiles, n_blocks = p.n_blocks, a_mode = p.a_mode;
+    const int sa_r = (int)p.sa_r, sb_r = (int)p.sb_r, sd_r = (int)p.sd_r;
+    const int64_t se_r = p.se_r;
+    const float c1 = p.c1;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = uniform(tid >> 6);
     const int c = lane & 31, g = lane >> 5;
     const int wr = wave / NS, wn = wave % NS;
 
@@ -103,98 +149,136 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     // m-tiles of one batch re-read that batch's B and D from one L2.
     int logical;
     {
-        const int hw = blockIdx.x, nb = p.n_blocks;
-        const int x = hw & 7, q = nb >> 3, rem = nb & 7;
+        const int hw = blockIdx.x;
+        const int x = hw & 7, q = n_blocks >> 3, rem = n_blocks & 7;
         logical = x * q + (x < rem ? x : rem) + (hw >> 3);
     }
-    const int batch = logical / p.m_tiles;
-    const int mt = logical - batch * p.m_tiles;
-    const int m0 = mt * TM + wr * (32 * MB);
+    const int batch = logical / m_tiles;
+    const int mt = logical - batch * m_tiles;
+    const int mrow0 = mt * TM; // first row of the block
 
-    const T *Ag = (const T *)p.A + batch * p.sa_b;
+    const T *Ag = (const T *)p.A + batch * p.sa_b + (int64_t)mrow0 * sa_r;
     const T *Bg = (const T *)p.B + batch * p.sb_b;
     const T *Dg = (const T *)p.D + batch * p.sd_b;
     T *Eg = (T *)p.E + batch * p.se_b;
+
+    // ---- per-lane byte offsets of the B / D pieces this wave loads for every n-tile ----------
+    // Wave-load j of a stage covers LDS bytes [1024 j, 1024 j + 1024): 16-byte slot 64 j + lane.
+    // Slot -> (row, stored chunk); the global source is the logical chunk = stored ^ swizzle.
+    // With clamp (the ragged last tile), rows / columns beyond N are redirected to valid memory
+    // (their contribution is masked in registers), so no load ever leaves the tensors.
+    auto bd_offset = [&](int u, int nt0, bool clamp) -> unsigned {
+        int j = wave + u * W;
+        j = j < CT ? j : CT - 1;
+        if (j < CB) {
+            const int slot = 64 * j + lane;
+            int row = slot / (RBB / 16), ch = slot % (RBB / 16);
+            if (BKC) {
+                ch ^= swz_b128(RBB, row);
+                if (clamp && nt0 + row >= N) row = N - 1 - nt0;
+            } else {
+                ch ^= swz_tr(RBB, row);
+                if (clamp && nt0 + 8 * ch >= N) ch = 0;
+            }
+            return (unsigned)(row * sb_r * 2 + ch * 16);
+        } else {
+            const int slot = 64 * (j - CB) + lane;
+            int row = slot / (RBD / 16), ch = slot % (RBD / 16);
+            ch ^= swz_tr(RBD, row);
+            if (clamp && nt0 + row >= N) row = N - 1 - nt0;
+            return (unsigned)(row * sd_r * 2 + ch * 16);
+        }
+    };
+    unsigned voff[P];
+#pragma unroll
+    for (int u = 0; u < P; ++u) voff[u] = bd_offset(u, 0, false);
+
+    const int n_iters = (N + TN - 1) / TN;
+    const int n_full = N / TN; // tiles [0, n_full) are complete, tile n_full (if any) is ragged
+
+    auto issue_tile = [&](int t, int stage) {
+        const int nt0 = t * TN;
+        const void *bbase = uniform((const void *)(BKC ? Bg + (int64_t)nt0 * sb_r : Bg + nt0));
+        const void *dbase = uniform((const void *)(Dg + (int64_t)nt0 * sd_r));
+        const unsigned dst0 = uniform(lds0 + stage * STAGE + wave * 1024);
+        if (t < n_full) {
+#pragma unroll
+            for (int u = 0; u < P; ++u) {
+                const int j = wave + u * W; // wave-uniform
+                const int jj = j < CT ? j : CT - 1;
+                dma16(dst0 + (jj - wave) * 1024, voff[u], jj < CB ? bbase : dbase);
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < P; ++u) {
+                const int j = wave + u * W;
+                const int jj = j < CT ? j : CT - 1;
+                dma16(dst0 + (jj - wave) * 1024, bd_offset(u, nt0, true), jj < CB ? bbase : dbase);
+            }
+        }
+    };
+
+    // ---- prologue: A tile (into the last ring slot) and the first S-1 n-tiles ---------------
+    {
+        const void *abase = uniform((const void *)Ag);
+        const unsigned dst0 = uniform(lds0 + A_LDS + wave * 1024);
+#pragma unroll
+        for (int u = 0; u < PA; ++u) {
+            const int j = wave + u * W;
+            const int jj = j < CA ? j : CA - 1;
+            const int slot = 64 * jj + lane;
+            int row = slot / (RBA / 16), ch = slot % (RBA / 16);
+            ch ^= swz_b128(RBA, row);
+            if (mrow0 + row >= M) row = M - 1 - mrow0; // rows past M: any valid row, never stored
+            dma16(dst0 + (jj - wave) * 1024, (unsigned)(row * sa_r * 2 + ch * 16), abase);
+        }
+    }
+    const int n_pre = n_iters < S - 1 ? n_iters : S - 1;
+    for (int t = 0; t < n_pre; ++t) issue_tile(t, t);
+    // the A loads are older than the n_pre tile groups
+    if (n_pre == S - 1) wait_vm<(S - 1) * P>();
+    else wait_vm<0>();
+    __syncthreads();
 
     // ---- L_A: A tile -> registers, as the second MFMA operand A^T[k][m] ------------------
     v8 a[MB][KS];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
-        const int row = m0 + 32 * mb + c;
+        const int row = wr * (32 * MB) + 32 * mb + c;
+        const lds_u8 *src = smem + A_LDS + row * RBA;
+        const int sw = swz_b128(RBA, row);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            u32x4 raw = {0u, 0u, 0u, 0u};
-            if (row < p.M && p.a_mode != 2) raw = *(const u32x4 *)(Ag + (int64_t)row * p.sa_r + 16 * ks + 8 * g);
-            if (p.a_mode == 1) raw ^= 0x80008000u; // flip the sign of all eight 16-bit floats
+            u32x4 raw = *(const lds_u32x4 *)(src + 16 * ((2 * ks + g) ^ sw));
+            if (a_mode == 1) raw ^= 0x80008000u; // flip the sign of all eight 16-bit floats
+            if (a_mode == 2) raw = u32x4{0u, 0u, 0u, 0u};
             a[mb][ks] = __builtin_bit_cast(v8, raw);
         }
     }
 
-    // ---- per-thread source / destination of the B and D tile chunks ----------------------
-    // B tile: BKC  -> rows n (TN of them), KD contiguous k: chunk q -> (row q/(KD/8), col 8*(q%(KD/8)))
-    //         !BKC -> rows k (KD of them), TN contiguous n: chunk q -> (row q/(TN/8), col 8*(q%(TN/8)))
-    // D tile: rows n (TN), LD contiguous h.
-    u32x4 breg[B_PER_T], dreg[D_PER_T];
-
-    auto load_tiles = [&](int nt0) {
-#pragma unroll
-        for (int u = 0; u < B_PER_T; ++u) {
-            const int q = tid + u * NT;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (B_CHUNKS % NT == 0 || q < B_CHUNKS) {
-                if (BKC) {
-                    const int r = q / (KD / 8), cc = q % (KD / 8);
-                    if (nt0 + r < p.N) v = *(const u32x4 *)(Bg + (int64_t)(nt0 + r) * p.sb_r + 8 * cc);
-                } else {
-                    const int r = q / (TN / 8), cc = q % (TN / 8);
-                    if (nt0 + 8 * cc < p.N) v = *(const u32x4 *)(Bg + (int64_t)r * p.sb_r + nt0 + 8 * cc);
-                }
-            }
-            breg[u] = v;
-        }
-#pragma unroll
-        for (int u = 0; u < D_PER_T; ++u) {
-            const int q = tid + u * NT;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (D_CHUNKS % NT == 0 || q < D_CHUNKS) {
-                const int r = q / (LD / 8), cc = q % (LD / 8);
-                if (nt0 + r < p.N) v = *(const u32x4 *)(Dg + (int64_t)(nt0 + r) * p.sd_r + 8 * cc);
-            }
-            dreg[u] = v;
-        }
-    };
-    auto store_tiles = [&](int stage) {
-        unsigned char *sB = smem + stage * STAGE;
-        unsigned char *sD = sB + B_BYTES;
-#pragma unroll
-        for (int u = 0; u < B_PER_T; ++u) {
-            const int q = tid + u * NT;
-            if (B_CHUNKS % NT == 0 || q < B_CHUNKS) {
-                const int r = BKC ? q / (KD / 8) : q / (TN / 8);
-                const int cc = BKC ? q % (KD / 8) : q % (TN / 8);
-                *(u32x4 *)(sB + r * PB + 16 * cc) = breg[u];
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < D_PER_T; ++u) {
-            const int q = tid + u * NT;
-            if (D_CHUNKS % NT == 0 || q < D_CHUNKS) {
-                const int r = q / (LD / 8), cc = q % (LD / 8);
-                *(u32x4 *)(sD + r * PD + 16 * cc) = dreg[u];
-            }
-        }
-    };
-
     // ---- loop-invariant LDS read offsets of this lane --------------------------------------
     const int i16 = lane & 15, u16 = (lane >> 4) & 1;
-    // B operand of GEMM 1 (first MFMA operand B^T[n][k]): n = wn*32 + c, k = 16ks + 8g + 0..7
-    const int b_off = BKC ? (wn * 32 + c) * PB + 16 * g
-                          : (8 * g + (i16 >> 2)) * PB + (wn * 32 + 16 * u16 + 4 * (i16 & 3)) * 2;
+    int b_off;
+    if (BKC) {
+        // first MFMA operand B^T[n][k]: row n = wn*32 + c, logical chunk 2ks + g
+        const int row = wn * 32 + c;
+        b_off = row * RBB + 16 * (g ^ swz_b128(RBB, row)); // per k-step: ^ (32 ks)
+    } else {
+        // rows k = 16ks + 8g + i/4 (+4), columns n = wn*32 + 16u + 4(i%4) .. +3
+        const int row = 8 * g + (i16 >> 2);
+        const int ch = (4 * wn + 2 * u16 + ((i16 >> 1) & 1)) ^ swz_tr(RBB, row);
+        b_off = row * RBB + 16 * ch + 8 * (i16 & 1);
+    }
     // D operand of GEMM 2 (first MFMA operand D^T[h][n]).  MFMA row i of the h block is mapped
     // to h = 16*((i>>2)&1) + 4*(i>>3) + (i&3) so that the accumulator of lane (c,g) ends up
     // holding 16 consecutive h:  h = 32hb + 16g + r.
-    const int x4 = i16 & 3;
-    const int d_off = (wn * 32 + 4 * g + (i16 >> 2)) * PD + (8 * u16 + 16 * (x4 & 1) + 4 * (x4 >> 1)) * 2;
+    int d_off;
+    {
+        const int x4 = i16 & 3;
+        const int row = wn * 32 + 4 * g + (i16 >> 2);
+        const int ch = (u16 + 2 * (x4 & 1)) ^ swz_tr(RBD, row); // h block 0; per hb: ^ (64 hb) bytes
+        d_off = B_BYTES + row * RBD + 16 * ch + 8 * (x4 >> 1);
+    }
 
     f32x16 accE[MB][HB];
     float m_run[MB], l_run[MB];
@@ -208,23 +292,24 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             for (int r = 0; r < 16; ++r) accE[mb][hb][r] = 0.f;
     }
 
-    const int n_iters = (p.N + TN - 1) / TN;
-    if (n_iters > 0) {
-        load_tiles(0);
-        store_tiles(0);
-    }
-    __syncthreads();
-
+    int stage_c = 0;     // ring slot of the tile being consumed
+    int stage_l = S - 1; // ring slot the next issued tile goes to
     for (int it = 0; it < n_iters; ++it) {
-        const int nt0 = it * TN;
-        const bool more = it + 1 < n_iters;
-        if (more) load_tiles(nt0 + TN); // global loads in flight during the MFMAs below
+        // Tiles it .. min(it+S-2, n_iters-1) are in flight.  Retire tile `it`: in the steady
+        // state S-2 younger groups may stay in flight, near the end simply drain.
+        if (n_iters - it >= S - 1) wait_vm<(S - 2) * P>();
+        else wait_vm<0>();
+        __syncthreads(); // tile `it` is complete for every wave; the slot of tile it-1 is free
+        if (it + S - 1 < n_iters) {
+            issue_tile(it + S - 1, stage_l);
+            stage_l = stage_l + 1 == S ? 0 : stage_l + 1;
+        }
 
-        const unsigned char *sB = smem + (it & 1) * STAGE;
-        const unsigned char *sD = sB + B_BYTES;
-        const int n0 = nt0 + wn * 32; // first column of this wave's 32-wide slice
+        const lds_u8 *sT = smem + stage_c * STAGE;
+        stage_c = stage_c + 1 == S ? 0 : stage_c + 1;
+        const int n0 = it * TN + wn * 32; // first column of this wave's 32-wide slice
 
-        if (n0 < p.N) {
+        if (n0 < N) {
             // ---- C_C: C^T[n][m] = sum_k B^T[n][k] A^T[k][m] ---------------------------------
             f32x16 accC[MB];
 #pragma unroll
@@ -235,10 +320,10 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             for (int ks = 0; ks < KS; ++ks) {
                 v8 bop;
                 if (BKC) {
-                    bop = __builtin_bit_cast(v8, *(const u32x4 *)(sB + b_off + 32 * ks));
+                    bop = __builtin_bit_cast(v8, *(const lds_u32x4 *)(sT + (b_off ^ (32 * ks))));
                 } else {
-                    i16x4 lo = lds_read_tr(sB + b_off + (16 * ks) * PB);
-                    i16x4 hi = lds_read_tr(sB + b_off + (16 * ks + 4) * PB);
+                    i16x4 lo = lds_read_tr(sT + b_off + (16 * ks) * RBB);
+                    i16x4 hi = lds_read_tr(sT + b_off + (16 * ks + 4) * RBB);
                     i16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                     bop = __builtin_bit_cast(v8, both);
                 }
@@ -252,23 +337,23 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
                 f32x16 s = accC[mb];
-                if (SOFTMAX) {
-                    if (n0 + 32 > p.N) {
+                if (n0 + 32 > N) { // ragged last tile: columns past N contribute nothing
 #pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            if (n0 + 8 * (r / 4) + 4 * g + (r % 4) >= p.N) s[r] = -INFINITY;
-                    }
+                    for (int r = 0; r < 16; ++r)
+                        if (n0 + 8 * (r / 4) + 4 * g + (r % 4) >= N) s[r] = SOFTMAX ? -INFINITY : 0.f;
+                }
+                if (SOFTMAX) {
                     float mx = s[0];
 #pragma unroll
                     for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
                     mx = xhalf_max(mx);
                     const float m_new = fmaxf(m_run[mb], mx);
-                    const float corr = __builtin_amdgcn_exp2f((m_run[mb] - m_new) * p.c1);
-                    const float mneg = -m_new * p.c1;
+                    const float corr = __builtin_amdgcn_exp2f((m_run[mb] - m_new) * c1);
+                    const float mneg = -m_new * c1;
                     float sum = 0.f;
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        s[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], p.c1, mneg));
+                        s[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c1, mneg));
                         sum += s[r];
                     }
                     l_run[mb] = l_run[mb] * corr + sum;
@@ -291,9 +376,9 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             for (int hb = 0; hb < HB; ++hb) {
 #pragma unroll
                 for (int qp = 0; qp < 2; ++qp) {
-                    const unsigned char *src = sD + d_off + (16 * qp) * PD + 64 * hb;
+                    const lds_u8 *src = sT + ((d_off ^ (64 * hb)) + (16 * qp) * RBD);
                     i16x4 lo = lds_read_tr(src);
-                    i16x4 hi = lds_read_tr(src + 8 * PD);
+                    i16x4 hi = lds_read_tr(src + 8 * RBD);
                     i16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                     v8 dop = __builtin_bit_cast(v8, both);
 #pragma unroll
@@ -301,9 +386,6 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
                 }
             }
         }
-
-        if (more) store_tiles((it + 1) & 1);
-        __syncthreads();
     }
 
     // ---- finish the softmax denominator -----------------------------------------------------
@@ -312,12 +394,14 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         for (int mb = 0; mb < MB; ++mb) l_run[mb] = xhalf_sum(l_run[mb]);
     }
 
+    __syncthreads(); // every wave is done reading the ring: its space is reused below
+
     // ---- combine the ns partial results of a row-group (waves wn > 0 -> wave wn == 0) -------
     if (NS > 1) {
         constexpr int PER_MB = HB * 16 + 2; // floats per lane per mb
-        float *scratch = (float *)smem;     // staging buffers are dead after the last barrier
+        lds_f32 *scratch = (lds_f32 *)smem;
         if (wn > 0) {
-            float *dst = scratch + ((wr * (NS - 1) + (wn - 1)) * MB) * PER_MB * 64 + lane;
+            lds_f32 *dst = scratch + ((wr * (NS - 1) + (wn - 1)) * MB) * PER_MB * 64 + lane;
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
@@ -332,7 +416,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         if (wn == 0) {
 #pragma unroll
             for (int w = 1; w < NS; ++w) {
-                const float *src = scratch + ((wr * (NS - 1) + (w - 1)) * MB) * PER_MB * 64 + lane;
+                const lds_f32 *src = scratch + ((wr * (NS - 1) + (w - 1)) * MB) * PER_MB * 64 + lane;
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb) {
                     float f_own = 1.f, f_oth = 1.f;
@@ -341,8 +425,8 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
                         const float l_o = src[(mb * PER_MB + HB * 16 + 1) * 64];
                         const float m_new = fmaxf(m_run[mb], m_o);
                         // a wave that saw no column has m = -inf, l = 0 and a zero accumulator
-                        f_own = (m_run[mb] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_run[mb] - m_new) * p.c1);
-                        f_oth = (m_o == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_o - m_new) * p.c1);
+                        f_own = (m_run[mb] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_run[mb] - m_new) * c1);
+                        f_oth = (m_o == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_o - m_new) * c1);
                         l_run[mb] = l_run[mb] * f_own + l_o * f_oth;
                         m_run[mb] = m_new;
                     }
@@ -358,26 +442,39 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         }
     }
 
-    // ---- S_E: E tile -> global.  Lane (c,g) holds E[m0+32mb+c][32hb + 16g + 0..15]. ----------
+    // ---- S_E: E tile -> global ------------------------------------------------------------
+    // Lane (c,g) holds E[row c][32hb + 16g + 0..15].  The wave's 32*MB x L tile is staged in
+    // LDS (swizzled) and read back so that consecutive lanes store consecutive 16-byte pieces
+    // of a row: every store instruction writes whole 2L-byte rows.
     if (NS == 1 || wn == 0) {
+        lds_u8 *es = smem + combine_bytes(LD, MB, RG, NS) + wr * (32 * MB * RBE);
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-            const int row = m0 + 32 * mb + c;
+            const int row = 32 * mb + c;
             const float inv = SOFTMAX ? 1.0f / l_run[mb] : 1.0f;
-            if (row < p.M) {
-                T *dst = Eg + (int64_t)row * p.se_r + 16 * g;
+            const int sw = swz_b128(RBE, row);
 #pragma unroll
-                for (int hb = 0; hb < HB; ++hb) {
-                    v8 lo, hi;
+            for (int hb = 0; hb < HB; ++hb) {
+                v8 lo, hi;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        lo[e] = (T)(accE[mb][hb][e] * inv);
-                        hi[e] = (T)(accE[mb][hb][8 + e] * inv);
-                    }
-                    *(u32x4 *)(dst + 32 * hb) = __builtin_bit_cast(u32x4, lo);
-                    *(u32x4 *)(dst + 32 * hb + 8) = __builtin_bit_cast(u32x4, hi);
+                for (int e = 0; e < 8; ++e) {
+                    lo[e] = (T)(accE[mb][hb][e] * inv);
+                    hi[e] = (T)(accE[mb][hb][8 + e] * inv);
                 }
+                *(lds_u32x4 *)(es + row * RBE + 16 * ((4 * hb + 2 * g) ^ sw)) = __builtin_bit_cast(u32x4, lo);
+                *(lds_u32x4 *)(es + row * RBE + 16 * ((4 * hb + 2 * g + 1) ^ sw)) = __builtin_bit_cast(u32x4, hi);
             }
+        }
+        constexpr int CPR = RBE / 16;               // 16-byte pieces per row
+        constexpr int PASSES = 32 * MB * CPR / 64;  // wave-wide stores for the tile
+        const int rbase = mrow0 + wr * (32 * MB);
+#pragma unroll
+        for (int ps = 0; ps < PASSES; ++ps) {
+            const int slot = 64 * ps + lane;
+            const int row = slot / CPR;
+            const int ch = (slot % CPR) ^ swz_b128(RBE, row);
+            const u32x4 v = *(const lds_u32x4 *)(es + 16 * slot);
+            if (rbase + row < M) *(u32x4 *)(Eg + (int64_t)(rbase + row) * se_r + 8 * ch) = v;
         }
     }
 }
@@ -385,15 +482,15 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
 // Host-side launcher of one instantiation.
 template <typename T, int KD, int LD, int MB, int RG, int NS, bool SOFTMAX, bool BKC>
 int launch_chain(const KParams &p, void *stream) {
-    constexpr int LDS = total_lds_bytes(KD, LD, MB, RG, NS, BKC);
+    constexpr int lds = total_lds_bytes(KD, LD, MB, RG, NS, ring_stages(KD, LD, MB, RG, NS));
     auto kern = chain_kernel<T, KD, LD, MB, RG, NS, SOFTMAX, BKC>;
     static bool attr_done = false; // benign race: setting the attribute twice is harmless
-    if (LDS > 64 * 1024 && !attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    if (lds > 64 * 1024 && !attr_done) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return (int)e;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(p.n_blocks), dim3(64 * RG * NS), LDS, (hipStream_t)stream, p);
+    hipLaunchKernelGGL(kern, dim3(p.n_blocks), dim3(64 * RG * NS), lds, (hipStream_t)stream, p);
     return (int)hipGetLastError();
 }
 

@@ -49,6 +49,9 @@ int decode_layout(const mcf_problem *p, Layout *o) {
     for (int t = 0; t < 4; ++t)
         if (lead[t] % 8 != 0 || bstr[t] % 8 != 0) return MCF_EALIGN;
     if (!o->b_kcontig && p->N % 8 != 0) return MCF_EUNSUPPORTED;
+    // the kernels address a tile with 32-bit byte offsets from a 64-bit tile base
+    for (int t = 0; t < 4; ++t)
+        if (lead[t] >= (1ll << 21)) return MCF_EUNSUPPORTED;
     return MCF_OK;
 }
 

@@ -1,36 +1,56 @@
-// Tile geometry shared by the kernels and the host-side budget checks: LDS row pitches and
-// sizes.  Plain constexpr C++, no HIP.
+// Tile geometry shared by the kernels and the host-side budget checks: tile byte sizes, the
+// XOR swizzles of the LDS layouts and the LDS total.  Plain constexpr C++, no HIP.
 #pragma once
 
 namespace mcf {
 
-// Row pitch in bytes of an LDS tile that is read with the transposing 64-bit LDS read
-// (rows of `elems` 16-bit elements).  Half a wave reads 4 rows x 64 B at once; an odd
-// multiple of 64 B puts those four pieces on disjoint banks.
-constexpr int pitch_tr(int elems) {
-    int p = elems * 2;
-    return (p % 128 == 64) ? p : (p / 128) * 128 + 64 + ((p % 128 > 64) ? 128 : 0);
+// All LDS tiles keep their natural row pitch (row bytes RB, a power of two >= 64) and are
+// filled by direct global->LDS loads in units of 16-byte chunks; bank conflicts are avoided
+// by XOR-ing the chunk index within a row with a function of the row.
+//
+// Tiles read with plain 128-bit reads (A tile; B tile when K is contiguous): 16 consecutive
+// rows are read at the same logical chunk, so consecutive rows must land on distinct 16-byte
+// bank groups of the 256-byte LDS line.
+constexpr int swz_b128(int row_bytes, int row) {
+    return row_bytes == 64 ? ((row >> 2) & 3) : row_bytes == 128 ? ((row >> 1) & 7) : (row & 15);
+}
+// Tiles read with the transposing 64-bit read (D tile; B tile when N is contiguous): half a
+// wave reads 4 consecutive rows x 64 bytes, so the four rows must land on distinct 64-byte
+// groups.  Returned as a chunk mask (multiple of 4 chunks = 64 bytes).
+constexpr int swz_tr(int row_bytes, int row) {
+    return row_bytes == 64 ? 0 : row_bytes == 128 ? 4 * ((row >> 1) & 1) : 4 * (row & 3);
 }
 
-// Row pitch in bytes of the K-contiguous B tile (read with plain 128-bit LDS reads).
-constexpr int pitch_bk(int K) { return K * 2 + 16; }
-
-constexpr int b_tile_bytes(int K, int tn, bool b_kcontig) {
-    return b_kcontig ? tn * pitch_bk(K) : K * pitch_tr(tn);
-}
-constexpr int d_tile_bytes(int L, int tn) { return tn * pitch_tr(L); }
-constexpr int stage_bytes(int K, int L, int tn, bool b_kcontig) {
-    return b_tile_bytes(K, tn, b_kcontig) + d_tile_bytes(L, tn);
-}
+constexpr int a_tile_bytes(int K, int mb, int rg) { return 32 * mb * rg * K * 2; }
+constexpr int b_tile_bytes(int K, int tn) { return K * tn * 2; }
+constexpr int d_tile_bytes(int L, int tn) { return tn * L * 2; }
+constexpr int stage_bytes(int K, int L, int tn) { return b_tile_bytes(K, tn) + d_tile_bytes(L, tn); }
 // Scratch for the cross-wave combine when ns > 1: per row-group, (ns-1) waves park their E
 // accumulators (fp32) and softmax state.
 constexpr int combine_bytes(int L, int mb, int rg, int ns) {
     return ns > 1 ? rg * (ns - 1) * mb * ((L / 32) * 16 + 2) * 64 * 4 : 0;
 }
-constexpr int total_lds_bytes(int K, int L, int mb, int rg, int ns, bool b_kcontig) {
-    int s = 2 * stage_bytes(K, L, 32 * ns, b_kcontig);
-    int c = combine_bytes(L, mb, rg, ns);
+// `stages` ring buffers of one B + D tile each; the A tile is staged in the last ring slot
+// (it is consumed before that slot is first filled); after the loop the ring space is reused
+// by the combine scratch followed by the staging tiles of the E store.
+constexpr int estage_bytes(int L, int mb, int rg) { return rg * 32 * mb * L * 2; }
+constexpr int total_lds_bytes(int K, int L, int mb, int rg, int ns, int stages) {
+    const int st = stage_bytes(K, L, 32 * ns);
+    const int a = a_tile_bytes(K, mb, rg);
+    int s = (stages - 1) * st + (a > st ? a : st);
+    const int c = combine_bytes(L, mb, rg, ns) + estage_bytes(L, mb, rg);
     return s > c ? s : c;
 }
+// Largest ring depth (2..4) that keeps a block within `budget` bytes of LDS.
+constexpr int pick_stages(int K, int L, int mb, int rg, int ns, int budget) {
+    int s = 4;
+    while (s > 2 && total_lds_bytes(K, L, mb, rg, ns, s) > budget) --s;
+    return s;
+}
+
+// Ring depth every kernel variant is built with: as deep as fits 80 KiB, so that two blocks
+// can share the 160 KiB LDS of a compute unit.
+constexpr int kLdsRingBudget = 80 * 1024;
+constexpr int ring_stages(int K, int L, int mb, int rg, int ns) { return pick_stages(K, L, mb, rg, ns, kLdsRingBudget); }
 
 } // namespace mcf

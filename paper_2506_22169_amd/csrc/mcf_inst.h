@@ -14,7 +14,7 @@
     X(1, 4, 2)
 
 #define MCF_ROW(T, DT, K, L, mb, rg, ns, sm, bkc) \
-    {DT, K, L, mb, rg, ns, sm, bkc, mcf::total_lds_bytes(K, L, mb, rg, ns, bkc), &mcf::launch_chain<T, K, L, mb, rg, ns, sm, bkc>},
+    {DT, K, L, mb, rg, ns, sm, bkc, &mcf::launch_chain<T, K, L, mb, rg, ns, sm, bkc>},
 
 #define MCF_DEFINE_GROUP(T, DT, K, L, NAME)                                      \
     namespace mcf {                                                              \

@@ -35,7 +35,6 @@ struct Variant {
     int32_t dtype, K, L;
     int32_t mb, rg, ns;
     int32_t softmax, b_kcontig;
-    int32_t lds_bytes;
     LaunchFn launch;
 };
 
@@ -50,8 +49,9 @@ struct Layout {
 };
 int decode_layout(const mcf_problem *p, Layout *out); // MCF_OK or an error status
 
-// LDS bytes a variant needs (two stages of a B tile and a D tile, padded rows).
-int lds_bytes_for(int K, int L, int mb, int rg, int ns, int b_kcontig);
+// Ring depth and LDS bytes of a variant; register estimate per lane.
+int stages_for(int K, int L, int mb, int rg, int ns);
+int lds_bytes_for(int K, int L, int mb, int rg, int ns, int stages);
 int vgpr_estimate(int K, int L, int mb, int rg, int ns, int softmax);
 
 void set_last_error(const char *msg);

@@ -15,7 +15,9 @@
 //   * eq. (1) sums all five tiles against shared memory.  Here C and E (and A) live in
 //     registers, so the sum is split: B and D tiles (two stages, padded rows) against the
 //     160 KiB LDS, and A, C, E tiles against the 512-VGPR budget of a lane.  Both estimates
-//     are exact for hand-written kernels, so the 1.2x slack of Rule 4 is not applied.
+//     are exact for hand-written kernels, so the 1.2x slack of Rule 4 is not applied.  The LDS
+//     holds a ring of 2..4 (B tile + D tile) stages, as deep as fits 80 KiB so that two
+//     blocks share a compute unit.
 //   * N_SM of eq. (5) is the number of compute units (256).
 #include <math.h>
 #include <string.h>
@@ -25,17 +27,15 @@
 
 namespace mcf {
 
-int lds_bytes_for(int K, int L, int mb, int rg, int ns, int b_kcontig) {
-    return total_lds_bytes(K, L, mb, rg, ns, b_kcontig != 0);
-}
+int stages_for(int K, int L, int mb, int rg, int ns) { return ring_stages(K, L, mb, rg, ns); }
+int lds_bytes_for(int K, int L, int mb, int rg, int ns, int stages) { return total_lds_bytes(K, L, mb, rg, ns, stages); }
 
 // Registers per lane: A tile (mb*K/16 operands of 4 VGPRs), E accumulators (mb * L/32 * 16),
-// one C accumulator and its 16-bit copy per mb, the staged global->LDS chunks, and a fixed
-// allowance for addresses and softmax state.
+// one C accumulator and its 16-bit copy per mb, one load offset per wave-load of a stage, and
+// a fixed allowance for operands in flight, addresses and softmax state.
 int vgpr_estimate(int K, int L, int mb, int rg, int ns, int softmax) {
-    const int nt = 64 * rg * ns, tn = 32 * ns;
-    const int staged = ((K * tn / 8 + nt - 1) / nt + (tn * L / 8 + nt - 1) / nt) * 4;
-    return mb * (K / 16) * 4 + mb * (L / 32) * 16 + mb * (16 + 8) + staged + 40 + (softmax ? 24 : 0);
+    const int loads = (stage_bytes(K, L, 32 * ns) / 1024 + rg * ns - 1) / (rg * ns);
+    return mb * (K / 16) * 4 + mb * (L / 32) * 16 + mb * (16 + 8) + loads + 40 + (softmax ? 24 : 0);
 }
 
 static bool is_pow2(int64_t x) { return x > 0 && (x & (x - 1)) == 0; }
@@ -52,7 +52,9 @@ static void eval_model(const mcf_problem *p, int softmax, int b_kcontig, int mb,
     t->mb = mb; t->rg = rg; t->ns = ns;
     t->tm = 32 * mb * rg; t->tn = 32 * ns; t->tk = (int32_t)p->K; t->tl = (int32_t)p->L;
     t->waves = rg * ns;
-    t->lds_bytes = lds_bytes_for((int)p->K, (int)p->L, mb, rg, ns, b_kcontig);
+    t->stages = stages_for((int)p->K, (int)p->L, mb, rg, ns);
+    t->lds_bytes = lds_bytes_for((int)p->K, (int)p->L, mb, rg, ns, t->stages);
+    (void)b_kcontig;
     t->vgpr_est = vgpr_estimate((int)p->K, (int)p->L, mb, rg, ns, softmax);
     const int64_t es = 2; // bytes per element, fp16 / bf16
     const int64_t m = (p->M + t->tm - 1) / t->tm, n = (p->N + t->tn - 1) / t->tn;
