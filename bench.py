@@ -35,11 +35,15 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="cfg2", help="cfg1..cfg5 (default: cfg2, the configuration the metric is quoted on)")
-    ap.add_argument("--tiles", default=None, help="mb,rg,ns to override the picker")
+    ap.add_argument("--tiles", default=None, help="mb,rg,ns,nj to override the picker")
     ap.add_argument("--eager", action="store_true", help="time plain calls instead of a HIP graph replay")
     ap.add_argument("--warm", action="store_true", help="reuse one buffer set (cache-resident operands)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--traffic", default=None, help="JSON file with measured HBM bytes per launch (from the rocprofv3 --pmc runs)")
+    ap.add_argument("--copy-ref", type=int, default=0, metavar="MiB",
+                    help="after the timed region also run one plain device copy of this many MiB (the "
+                         "known-size kernel that calibrates the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--traffic", default=os.path.join(ROOT, "profiles", "traffic.json"),
+                    help="JSON file with measured HBM bytes per launch (from the rocprofv3 --pmc runs)")
     return ap.parse_args()
 
 
@@ -129,6 +133,14 @@ def main():
     t_step = wall_s / args.steps          # whole-job figure: host clock around the region
     t_kernel = dev_s / args.steps         # HIP events on the launch stream: average per launch
 
+    if args.copy_ref:
+        n = args.copy_ref * 2**20 // 2
+        src = torch.ones(n, dtype=torch.float16, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+
     gbs = per_set / t_step / 1e9
     tflops = w.flops / t_step / 1e12
     ai = w.flops / per_set
@@ -187,7 +199,8 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: batch={w.batch} M={w.M} K={w.K} N={w.N} L={w.L} {w.dtype}"
                                f"{' softmax' if w.softmax else ''}",
-                   "tiles": {"mb": picked.mb, "rg": picked.rg, "ns": picked.ns, "tm": picked.tm, "tn": picked.tn},
+                   "tiles": {"mb": picked.mb, "rg": picked.rg, "ns": picked.ns, "nj": picked.nj, "tm": picked.tm,
+                             "tn": picked.tn, "stages": picked.stages},
                    "buffer_sets": n_sets, "launch": "eager" if args.eager else "hip_graph"},
         "pct_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS, "tflops": tflops,
         "pct_mfma_peak": 100.0 * tflops / MFMA_PEAK_TFLOPS,

@@ -63,15 +63,19 @@ typedef struct mcf_problem {
  * and L_A / S_E are hoisted out of the n loop, Sec. III-B):
  *     block <-> (batch, m-tile);   L_A;  for n-tile: { L_B, L_D -> LDS; C_C; [softmax]; C_E };  S_E
  * tm = 32 * mb * rg rows per block (rg wave row-groups, each wave owning 32*mb rows),
- * tn = 32 * ns columns per n-iteration (ns waves side by side in n), waves = rg * ns.
+ * tn = 32 * ns * nj columns per n-iteration (ns waves side by side in n, each owning nj
+ * 32-column slices), waves = rg * ns.
  */
 typedef struct mcf_tiles {
     int32_t tm, tn, tk, tl;   /* tile sizes T_M, T_N, T_K (= K), T_L (= L)                       */
-    int32_t mb, rg, ns;       /* 32-row blocks per wave, wave row-groups, waves across n         */
+    int32_t mb, rg, ns, nj;   /* 32-row blocks per wave, wave row-groups, waves across n,        */
+                              /* 32-column slices per wave and n-iteration (0 reads as 1)        */
     int32_t waves;            /* rg * ns, 64 lanes each                                          */
     int32_t stages;           /* depth of the LDS ring of (B tile + D tile) buffers, 2..4        */
     int32_t lds_bytes;        /* eq. (1) restricted to the tiles held in LDS (B, D; x stages)    */
     int32_t vgpr_est;         /* eq. (1) restricted to the tiles held in registers (A, C, E)     */
+    int32_t vgpr_used;        /* registers per lane the compiler allocated for this variant      */
+    int32_t scratch_bytes;    /* per-lane spill space of the variant (non-zero: never picked)    */
     int64_t blocks;           /* N_block of eq. (5)                                              */
     int64_t compulsory_bytes; /* A, B, D read once + E written once                              */
     int64_t model_bytes;      /* numerator of eq. (3): sum of tile bytes x trip counts           */
@@ -88,19 +92,20 @@ typedef struct mcf_tiles {
 int mcf_pick_tiles(const mcf_problem *problem, int softmax, mcf_tiles *out);
 
 /*
- * Evaluate the model for a caller-chosen (mb, rg, ns) instead of picking: fills every other
+ * Evaluate the model for a caller-chosen (mb, rg, ns, nj) instead of picking: fills every other
  * field of *tiles.  MCF_EUNSUPPORTED if no built variant has that shape, MCF_EINVAL if it
- * breaks a budget.  Host only.
+ * breaks a budget (LDS, registers) -- such a variant still runs unless it exceeds the LDS of
+ * a compute unit.  Host only.
  */
 int mcf_eval_tiles(const mcf_problem *problem, int softmax, mcf_tiles *tiles);
 
-/* Number of built kernel variants and their (mb, rg, ns) for the shape; host only.
- * Writes up to cap triples into mb_rg_ns (3 ints each) and returns the total count. */
-int mcf_list_variants(const mcf_problem *problem, int softmax, int32_t *mb_rg_ns, int cap);
+/* Number of built kernel variants and their (mb, rg, ns, nj) for the shape; host only.
+ * Writes up to cap quadruples into shapes (4 ints each) and returns the total count. */
+int mcf_list_variants(const mcf_problem *problem, int softmax, int32_t *shapes, int cap);
 
 /*
  * E = (A . B) . D   (Sec. III-A).  Device pointers; tiles_or_null == NULL means
- * mcf_pick_tiles() decides, otherwise only its mb, rg, ns fields are read.  hip_stream is a
+ * mcf_pick_tiles() decides, otherwise only its mb, rg, ns, nj fields are read.  hip_stream is a
  * hipStream_t (NULL = the default stream).  E must not overlap A, B or D.  batch, M or L of
  * zero is a no-op; N == 0 writes zeros.
  */

@@ -17,6 +17,10 @@ Readings taken where the text is ambiguous or at odds with itself:
     "a factor of k", but in that expression S_E sits in the scope of n, not k; by the volume
     rule stated two sentences earlier the saving is the extent of n.  volume() follows the rule.
   * "tile size" in eq. (1) and (3) is taken in bytes (elements * element size).
+  * The dead-loop rule of Sec. III-B would hoist a load out of every loop once all loops that
+    index its tensor have extent 1 (e.g. L_B when T_N = N and T_K = K).  Blocks share no
+    on-chip memory, so in estimate() no statement leaves the loops bound to the block index
+    (m, h and the batch): each block still loads what it uses once.
 """
 from itertools import permutations
 from math import ceil
@@ -54,15 +58,17 @@ def n_candidates(M, N, K, H, granule=16):
     return n_expr * ceil(M / granule) * ceil(N / granule) * ceil(K / granule) * ceil(H / granule)
 
 
-def _scope(order, related, extents, drop_unit_loops):
+def _scope(order, related, extents, drop_unit_loops, block_loops=""):
     """Loops surrounding a statement placed at the rightmost loop of `order` that is in
-    `related`; with drop_unit_loops, loops of extent 1 are dead nodes and cannot hold it."""
+    `related`; with drop_unit_loops, loops of extent 1 are dead nodes and cannot hold it.
+    Loops in block_loops are bound to the block index (Rule 1): a statement cannot be hoisted
+    out of them, because thread blocks share no on-chip memory."""
     live = [l for l in order if not (drop_unit_loops and extents[l] == 1)]
-    pos = max((live.index(l) for l in related if l in live), default=-1)
+    pos = max((live.index(l) for l in set(related) | set(block_loops) if l in live), default=-1)
     return live[:pos + 1]
 
 
-def trips(order, stmt, extents, hoist=True, drop_unit_loops=True):
+def trips(order, stmt, extents, hoist=True, drop_unit_loops=True, block_loops=""):
     """Trip count of a statement in the deep tiling `order` (a permutation of 'mnkh').
 
     stmt: 'C_C', 'C_E', 'L_A', 'L_B', 'L_D', 'S_E'.
@@ -70,11 +76,11 @@ def trips(order, stmt, extents, hoist=True, drop_unit_loops=True):
     association); hoist=True moves them to the rightmost loop that indexes their tensor.
     """
     if stmt.startswith("C_"):
-        scope = _scope(order, COMPUTE_LOOPS[stmt[2]], extents, drop_unit_loops)
+        scope = _scope(order, COMPUTE_LOOPS[stmt[2]], extents, drop_unit_loops, block_loops)
     else:
         tensor, comp = MEM_STATEMENTS[stmt]
         related = TENSOR_LOOPS[tensor] if hoist else COMPUTE_LOOPS[comp]
-        scope = _scope(order, related, extents, drop_unit_loops)
+        scope = _scope(order, related, extents, drop_unit_loops, block_loops)
     t = 1
     for l in scope:
         t *= extents[l]
@@ -119,10 +125,11 @@ def estimate(order, dims, tiles, batch, elem_bytes, W, P, n_units, W_reread=None
     W_reread None every byte is charged at W exactly as eq. (3) is printed.
     """
     ext = extents_of(dims, tiles)
-    mem = {s: volume(order, s, tiles, ext) * batch * elem_bytes for s in MEM_STATEMENTS}
+    blk = "mh"   # with the batch, the loops on the block index: nothing is hoisted out of a block
+    mem = {s: volume(order, s, tiles, ext, block_loops=blk) * batch * elem_bytes for s in MEM_STATEMENTS}
     flops = {
-        "C_C": 2 * tiles["m"] * tiles["n"] * tiles["k"] * trips(order, "C_C", ext) * batch,
-        "C_E": 2 * tiles["m"] * tiles["n"] * tiles["h"] * trips(order, "C_E", ext) * batch,
+        "C_C": 2 * tiles["m"] * tiles["n"] * tiles["k"] * trips(order, "C_C", ext, block_loops=blk) * batch,
+        "C_E": 2 * tiles["m"] * tiles["n"] * tiles["h"] * trips(order, "C_E", ext, block_loops=blk) * batch,
     }
     compulsory = batch * elem_bytes * (dims["m"] * dims["k"] + dims["k"] * dims["n"]
                                        + dims["n"] * dims["h"] + dims["m"] * dims["h"])

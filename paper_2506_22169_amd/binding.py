@@ -32,8 +32,9 @@ class Problem(ctypes.Structure):
 class Tiles(ctypes.Structure):
     """struct mcf_tiles"""
     _fields_ = [("tm", ctypes.c_int32), ("tn", ctypes.c_int32), ("tk", ctypes.c_int32), ("tl", ctypes.c_int32),
-                ("mb", ctypes.c_int32), ("rg", ctypes.c_int32), ("ns", ctypes.c_int32),
+                ("mb", ctypes.c_int32), ("rg", ctypes.c_int32), ("ns", ctypes.c_int32), ("nj", ctypes.c_int32),
                 ("waves", ctypes.c_int32), ("stages", ctypes.c_int32), ("lds_bytes", ctypes.c_int32), ("vgpr_est", ctypes.c_int32),
+                ("vgpr_used", ctypes.c_int32), ("scratch_bytes", ctypes.c_int32),
                 ("blocks", ctypes.c_int64), ("compulsory_bytes", ctypes.c_int64),
                 ("model_bytes", ctypes.c_int64), ("flops", ctypes.c_int64),
                 ("t_mem_s", ctypes.c_double), ("t_comp_s", ctypes.c_double),
@@ -147,9 +148,9 @@ def _tiles_arg(tiles):
         return None
     if isinstance(tiles, Tiles):
         return ctypes.byref(tiles)
-    mb, rg, ns = tiles
+    mb, rg, ns, nj = tiles
     t = Tiles()
-    t.mb, t.rg, t.ns = mb, rg, ns
+    t.mb, t.rg, t.ns, t.nj = mb, rg, ns, nj
     return ctypes.byref(t)
 
 
@@ -171,7 +172,7 @@ def _run(softmax, scale, A, B, D, out, tiles, stream):
 def gemm_chain(A, B, D, out=None, tiles=None, stream=None):
     """mcf_gemm_chain: E = (A . B) . D on device tensors A[b,M,K], B[b,K,N] (any of the two
     supported layouts, e.g. a transposed view of [b,N,K]), D[b,N,L].  tiles: None (picker),
-    a Tiles struct or an (mb, rg, ns) triple."""
+    a Tiles struct or an (mb, rg, ns, nj) tuple."""
     return _run(False, 1.0, A, B, D, out, tiles, stream)
 
 
@@ -187,18 +188,21 @@ def pick_tiles(problem, softmax=False):
     return t
 
 
-def eval_tiles(problem, mb, rg, ns, softmax=False):
+def eval_tiles(problem, mb, rg, ns, nj=1, softmax=False):
     """mcf_eval_tiles: model terms of a caller-chosen wave arrangement; host only."""
     t = Tiles()
-    t.mb, t.rg, t.ns = mb, rg, ns
-    _check(load_library().mcf_eval_tiles(ctypes.byref(problem), int(bool(softmax)), ctypes.byref(t)))
+    t.mb, t.rg, t.ns, t.nj = mb, rg, ns, nj
+    st = load_library().mcf_eval_tiles(ctypes.byref(problem), int(bool(softmax)), ctypes.byref(t))
+    if st not in (MCF_OK, 1):     # MCF_EINVAL = evaluated, but over a budget: terms are filled in
+        _check(st)
+    t.feasible = (st == MCF_OK)
     return t
 
 
 def list_variants(problem, softmax=False):
-    """mcf_list_variants: (mb, rg, ns) of every built kernel variant that covers the shape."""
+    """mcf_list_variants: (mb, rg, ns, nj) of every built kernel variant that covers the shape."""
     lib = load_library()
     n = lib.mcf_list_variants(ctypes.byref(problem), int(bool(softmax)), None, 0)
-    buf = (ctypes.c_int32 * (3 * max(n, 1)))()
+    buf = (ctypes.c_int32 * (4 * max(n, 1)))()
     lib.mcf_list_variants(ctypes.byref(problem), int(bool(softmax)), buf, n)
-    return [tuple(buf[3 * i:3 * i + 3]) for i in range(n)]
+    return [tuple(buf[4 * i:4 * i + 4]) for i in range(n)]

@@ -28,7 +28,7 @@
 //   result         Z[32 x 32]: lane holds Z[8(r/4) + 4g + r%4][c], r = 0..15
 //
 // Waves of a block form an rg x ns grid: wave (wr, wn) owns rows [wr*32*MB, +32*MB) of the
-// block's m-tile and columns [wn*32, +32) of every n-tile; with ns > 1 the partial results of
+// block's m-tile and NJ 32-column slices, columns [wn*32*NJ, +32*NJ), of every n-tile; with ns > 1 the partial results of
 // the ns waves of a row-group are combined through LDS after the loop.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -36,6 +36,16 @@
 
 #include "mcf_geometry.h"
 #include "mcf_internal.h"
+
+// Hook for cycle-stamp instrumentation in experiments; expands to nothing in the library.
+#ifndef MCF_TRACE_POINT
+#define MCF_TRACE_POINT(id)
+#endif
+// Compile-time ablation mask for experiments (0 in the library): 1 no operand reads from LDS,
+// 2 no MFMA, 4 no combine, 8 no E store, 16 no barrier in the loop, 32 no loads in the loop.
+#ifndef MCF_ABLATE
+#define MCF_ABLATE 0
+#endif
 
 namespace mcf {
 
@@ -104,16 +114,16 @@ static __device__ __forceinline__ const void *uniform(const void *q) {
     return (const void *)(((uint64_t)uniform((unsigned)(b >> 32)) << 32) | uniform((unsigned)b));
 }
 
-template <typename T, int KD, int LD, int MB, int RG, int NS, bool SOFTMAX, bool BKC>
+template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool BKC>
 __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     using M_ = Mfma<T>;
     using v8 = typename M_::v8;
     constexpr int W = RG * NS;           // waves per block
     constexpr int TM = 32 * MB * RG;     // rows per block
-    constexpr int TN = 32 * NS;          // columns per n-iteration
+    constexpr int TN = 32 * NS * NJ;     // columns per n-iteration
     constexpr int KS = KD / 16;          // MFMA k-steps of GEMM 1
     constexpr int HB = LD / 32;          // 32-wide h blocks of GEMM 2
-    constexpr int S = ring_stages(KD, LD, MB, RG, NS); // depth of the LDS ring
+    constexpr int S = ring_stages(KD, LD, MB, RG, NS, NJ); // depth of the LDS ring
     constexpr int RBA = 2 * KD;                  // row bytes of the A tile (rows m)
     constexpr int RBB = BKC ? 2 * KD : 2 * TN;   // row bytes of the B tile (rows n / rows k)
     constexpr int RBD = 2 * LD;                  // row bytes of the D tile (rows n)
@@ -162,6 +172,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     const T *Dg = (const T *)p.D + batch * p.sd_b;
     T *Eg = (T *)p.E + batch * p.se_b;
 
+    MCF_TRACE_POINT(0);
     // ---- per-lane byte offsets of the B / D pieces this wave loads for every n-tile ----------
     // Wave-load j of a stage covers LDS bytes [1024 j, 1024 j + 1024): 16-byte slot 64 j + lane.
     // Slot -> (row, stored chunk); the global source is the logical chunk = stored ^ swizzle.
@@ -235,10 +246,13 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     }
     const int n_pre = n_iters < S - 1 ? n_iters : S - 1;
     for (int t = 0; t < n_pre; ++t) issue_tile(t, t);
+    MCF_TRACE_POINT(1);
     // the A loads are older than the n_pre tile groups
     if (n_pre == S - 1) wait_vm<(S - 1) * P>();
     else wait_vm<0>();
+    MCF_TRACE_POINT(2);
     __syncthreads();
+    MCF_TRACE_POINT(3);
 
     // ---- L_A: A tile -> registers, as the second MFMA operand A^T[k][m] ------------------
     v8 a[MB][KS];
@@ -260,14 +274,14 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     const int i16 = lane & 15, u16 = (lane >> 4) & 1;
     int b_off;
     if (BKC) {
-        // first MFMA operand B^T[n][k]: row n = wn*32 + c, logical chunk 2ks + g
-        const int row = wn * 32 + c;
-        b_off = row * RBB + 16 * (g ^ swz_b128(RBB, row)); // per k-step: ^ (32 ks)
+        // first MFMA operand B^T[n][k]: row n = (wn*NJ + j)*32 + c, logical chunk 2ks + g
+        const int row = wn * NJ * 32 + c;
+        b_off = row * RBB + 16 * (g ^ swz_b128(RBB, row)); // per k-step: ^ (32 ks); per j: + 32 j rows
     } else {
-        // rows k = 16ks + 8g + i/4 (+4), columns n = wn*32 + 16u + 4(i%4) .. +3
+        // rows k = 16ks + 8g + i/4 (+4), columns n = (wn*NJ + j)*32 + 16u + 4(i%4) .. +3
         const int row = 8 * g + (i16 >> 2);
-        const int ch = (4 * wn + 2 * u16 + ((i16 >> 1) & 1)) ^ swz_tr(RBB, row);
-        b_off = row * RBB + 16 * ch + 8 * (i16 & 1);
+        const int ch = (4 * wn * NJ + 2 * u16 + ((i16 >> 1) & 1)) ^ swz_tr(RBB, row);
+        b_off = row * RBB + 16 * ch + 8 * (i16 & 1); // per j: ^ (64 j) bytes (NJ is a power of two)
     }
     // D operand of GEMM 2 (first MFMA operand D^T[h][n]).  MFMA row i of the h block is mapped
     // to h = 16*((i>>2)&1) + 4*(i>>3) + (i&3) so that the accumulator of lane (c,g) ends up
@@ -275,7 +289,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     int d_off;
     {
         const int x4 = i16 & 3;
-        const int row = wn * 32 + 4 * g + (i16 >> 2);
+        const int row = wn * NJ * 32 + 4 * g + (i16 >> 2); // per j: + 32 j rows
         const int ch = (u16 + 2 * (x4 & 1)) ^ swz_tr(RBD, row); // h block 0; per hb: ^ (64 hb) bytes
         d_off = B_BYTES + row * RBD + 16 * ch + 8 * (x4 >> 1);
     }
@@ -292,6 +306,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             for (int r = 0; r < 16; ++r) accE[mb][hb][r] = 0.f;
     }
 
+    MCF_TRACE_POINT(4);
     int stage_c = 0;     // ring slot of the tile being consumed
     int stage_l = S - 1; // ring slot the next issued tile goes to
     for (int it = 0; it < n_iters; ++it) {
@@ -299,63 +314,81 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         // state S-2 younger groups may stay in flight, near the end simply drain.
         if (n_iters - it >= S - 1) wait_vm<(S - 2) * P>();
         else wait_vm<0>();
-        __syncthreads(); // tile `it` is complete for every wave; the slot of tile it-1 is free
-        if (it + S - 1 < n_iters) {
+        MCF_TRACE_POINT(8 + 3 * (it & 7));
+        if (!(MCF_ABLATE & 16)) __syncthreads(); // tile `it` is complete for every wave; the slot of tile it-1 is free
+        if (it + S - 1 < n_iters && !(MCF_ABLATE & 32)) {
             issue_tile(it + S - 1, stage_l);
             stage_l = stage_l + 1 == S ? 0 : stage_l + 1;
         }
 
+        MCF_TRACE_POINT(9 + 3 * (it & 7));
         const lds_u8 *sT = smem + stage_c * STAGE;
         stage_c = stage_c + 1 == S ? 0 : stage_c + 1;
-        const int n0 = it * TN + wn * 32; // first column of this wave's 32-wide slice
+        const int n0 = it * TN + wn * (32 * NJ); // first column of this wave's 32*NJ-wide slice
 
         if (n0 < N) {
-            // ---- C_C: C^T[n][m] = sum_k B^T[n][k] A^T[k][m] ---------------------------------
-            f32x16 accC[MB];
+            // ---- C_C: C^T[n][m] = sum_k B^T[n][k] A^T[k][m], NJ independent 32-column slices ----
+            f32x16 accC[NJ][MB];
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) accC[mb][r] = 0.f;
+                for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                v8 bop;
-                if (BKC) {
-                    bop = __builtin_bit_cast(v8, *(const lds_u32x4 *)(sT + (b_off ^ (32 * ks))));
-                } else {
-                    i16x4 lo = lds_read_tr(sT + b_off + (16 * ks) * RBB);
-                    i16x4 hi = lds_read_tr(sT + b_off + (16 * ks + 4) * RBB);
-                    i16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    bop = __builtin_bit_cast(v8, both);
+                    for (int r = 0; r < 16; ++r) accC[j][mb][r] = 0.f;
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    v8 bop;
+                    if (MCF_ABLATE & 1) {
+                        bop = a[0][ks];
+                    } else if (BKC) {
+                        bop = __builtin_bit_cast(v8, *(const lds_u32x4 *)(sT + ((b_off ^ (32 * ks)) + 32 * j * RBB)));
+                    } else {
+                        const lds_u8 *src = sT + ((b_off ^ (64 * j)) + (16 * ks) * RBB);
+                        i16x4 lo = lds_read_tr(src);
+                        i16x4 hi = lds_read_tr(src + 4 * RBB);
+                        i16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                        bop = __builtin_bit_cast(v8, both);
+                    }
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) {
+                        if (MCF_ABLATE & 2) accC[j][mb][ks] += (float)bop[0] * (float)a[mb][ks][1];
+                        else accC[j][mb] = M_::run(bop, a[mb][ks], accC[j][mb]);
+                    }
                 }
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb) accC[mb] = M_::run(bop, a[mb][ks], accC[mb]);
             }
 
             // ---- softmax (online max / sum over n-tiles) and conversion to 16 bit -----------
-            // Lane (c,g) holds, for row m = c, the 16 columns n = n0 + 8(r/4) + 4g + r%4.
-            v8 pop[MB][2];
+            // Lane (c,g) holds, for row m = c, the columns n = n0 + 32j + 8(r/4) + 4g + r%4.
+            v8 pop[NJ][MB][2];
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
-                f32x16 s = accC[mb];
-                if (n0 + 32 > N) { // ragged last tile: columns past N contribute nothing
+                if (n0 + 32 * NJ > N) { // ragged last tile: columns past N contribute nothing
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (n0 + 8 * (r / 4) + 4 * g + (r % 4) >= N) s[r] = SOFTMAX ? -INFINITY : 0.f;
+                    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            if (n0 + 32 * j + 8 * (r / 4) + 4 * g + (r % 4) >= N) accC[j][mb][r] = SOFTMAX ? -INFINITY : 0.f;
                 }
                 if (SOFTMAX) {
-                    float mx = s[0];
+                    float mx = accC[0][mb][0];
 #pragma unroll
-                    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+                    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, accC[j][mb][r]);
                     mx = xhalf_max(mx);
                     const float m_new = fmaxf(m_run[mb], mx);
                     const float corr = __builtin_amdgcn_exp2f((m_run[mb] - m_new) * c1);
                     const float mneg = -m_new * c1;
                     float sum = 0.f;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        s[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c1, mneg));
-                        sum += s[r];
-                    }
+                    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            accC[j][mb][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(accC[j][mb][r], c1, mneg));
+                            sum += accC[j][mb][r];
+                        }
                     l_run[mb] = l_run[mb] * corr + sum;
                     m_run[mb] = m_new;
                     if (__builtin_amdgcn_ballot_w64(corr != 1.0f)) {
@@ -366,28 +399,42 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
                     }
                 }
 #pragma unroll
-                for (int qp = 0; qp < 2; ++qp)
+                for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) pop[mb][qp][e] = (T)s[8 * qp + e];
+                    for (int qp = 0; qp < 2; ++qp)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) pop[j][mb][qp][e] = (T)accC[j][mb][8 * qp + e];
             }
 
             // ---- C_E: E^T[h][m] += sum_n D^T[h][n] P^T[n][m] --------------------------------
 #pragma unroll
-            for (int hb = 0; hb < HB; ++hb) {
+            for (int j = 0; j < NJ; ++j) {
 #pragma unroll
-                for (int qp = 0; qp < 2; ++qp) {
-                    const lds_u8 *src = sT + ((d_off ^ (64 * hb)) + (16 * qp) * RBD);
-                    i16x4 lo = lds_read_tr(src);
-                    i16x4 hi = lds_read_tr(src + 8 * RBD);
-                    i16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    v8 dop = __builtin_bit_cast(v8, both);
+                for (int hb = 0; hb < HB; ++hb) {
 #pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) accE[mb][hb] = M_::run(dop, pop[mb][qp], accE[mb][hb]);
+                    for (int qp = 0; qp < 2; ++qp) {
+                        const lds_u8 *src = sT + ((d_off ^ (64 * hb)) + (32 * j + 16 * qp) * RBD);
+                        v8 dop;
+                        if (MCF_ABLATE & 1) {
+                            dop = a[0][(2 * hb + qp) % KS];
+                        } else {
+                            i16x4 lo = lds_read_tr(src);
+                            i16x4 hi = lds_read_tr(src + 8 * RBD);
+                            i16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                            dop = __builtin_bit_cast(v8, both);
+                        }
+#pragma unroll
+                        for (int mb = 0; mb < MB; ++mb) {
+                            if (MCF_ABLATE & 2) accE[mb][hb][qp] += (float)dop[0] * (float)pop[j][mb][qp][1];
+                            else accE[mb][hb] = M_::run(dop, pop[j][mb][qp], accE[mb][hb]);
+                        }
+                    }
                 }
             }
         }
     }
 
+    MCF_TRACE_POINT(5);
     // ---- finish the softmax denominator -----------------------------------------------------
     if (SOFTMAX) {
 #pragma unroll
@@ -397,7 +444,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     __syncthreads(); // every wave is done reading the ring: its space is reused below
 
     // ---- combine the ns partial results of a row-group (waves wn > 0 -> wave wn == 0) -------
-    if (NS > 1) {
+    if (NS > 1 && !(MCF_ABLATE & 4)) {
         constexpr int PER_MB = HB * 16 + 2; // floats per lane per mb
         lds_f32 *scratch = (lds_f32 *)smem;
         if (wn > 0) {
@@ -442,6 +489,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         }
     }
 
+    MCF_TRACE_POINT(6);
     // ---- S_E: E tile -> global ------------------------------------------------------------
     // Lane (c,g) holds E[row c][32hb + 16g + 0..15].  The wave's 32*MB x L tile is staged in
     // LDS (swizzled) and read back so that consecutive lanes store consecutive 16-byte pieces
@@ -474,16 +522,17 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             const int row = slot / CPR;
             const int ch = (slot % CPR) ^ swz_b128(RBE, row);
             const u32x4 v = *(const lds_u32x4 *)(es + 16 * slot);
-            if (rbase + row < M) *(u32x4 *)(Eg + (int64_t)(rbase + row) * se_r + 8 * ch) = v;
+            if (rbase + row < M && (!(MCF_ABLATE & 8) || v[0] == 0x12345u)) *(u32x4 *)(Eg + (int64_t)(rbase + row) * se_r + 8 * ch) = v;
         }
     }
+    MCF_TRACE_POINT(7);
 }
 
 // Host-side launcher of one instantiation.
-template <typename T, int KD, int LD, int MB, int RG, int NS, bool SOFTMAX, bool BKC>
+template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool BKC>
 int launch_chain(const KParams &p, void *stream) {
-    constexpr int lds = total_lds_bytes(KD, LD, MB, RG, NS, ring_stages(KD, LD, MB, RG, NS));
-    auto kern = chain_kernel<T, KD, LD, MB, RG, NS, SOFTMAX, BKC>;
+    constexpr int lds = total_lds_bytes(KD, LD, MB, RG, NS, NJ, ring_stages(KD, LD, MB, RG, NS, NJ));
+    auto kern = chain_kernel<T, KD, LD, MB, RG, NS, NJ, SOFTMAX, BKC>;
     static bool attr_done = false; // benign race: setting the attribute twice is harmless
     if (lds > 64 * 1024 && !attr_done) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -492,6 +541,16 @@ int launch_chain(const KParams &p, void *stream) {
     }
     hipLaunchKernelGGL(kern, dim3(p.n_blocks), dim3(64 * RG * NS), lds, (hipStream_t)stream, p);
     return (int)hipGetLastError();
+}
+
+// Launcher of an instantiation, or nullptr when the wave arrangement cannot exist for this
+// (K, L): more LDS than a compute unit has.  Such kernels are not compiled at all.
+template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool BKC>
+constexpr LaunchFn launcher_or_null() {
+    if constexpr (total_lds_bytes(KD, LD, MB, RG, NS, NJ, ring_stages(KD, LD, MB, RG, NS, NJ)) <= kLdsBytesPerBlock)
+        return &launch_chain<T, KD, LD, MB, RG, NS, NJ, SOFTMAX, BKC>;
+    else
+        return nullptr;
 }
 
 } // namespace mcf

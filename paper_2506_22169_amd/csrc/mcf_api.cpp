@@ -93,8 +93,11 @@ static int run(const mcf_problem *p, int softmax, float scale, const void *A, co
         st = mcf_pick_tiles(p, softmax, &chosen);
         if (st != MCF_OK) return st;
     }
-    const Variant *v = find_variant(p->in_dtype, (int)p->K, (int)p->L, softmax, lay.b_kcontig, chosen.mb, chosen.rg, chosen.ns);
+    const Variant *v = find_variant(p->in_dtype, (int)p->K, (int)p->L, softmax, lay.b_kcontig, chosen.mb, chosen.rg, chosen.ns, chosen.nj > 0 ? chosen.nj : 1);
     if (!v) return tiles ? MCF_EINVAL : MCF_EUNSUPPORTED;
+    if (lds_bytes_for((int)p->K, (int)p->L, v->mb, v->rg, v->ns, v->nj, stages_for((int)p->K, (int)p->L, v->mb, v->rg, v->ns, v->nj)) >
+        kLdsBytesPerBlock)
+        return MCF_EINVAL; // more LDS than a compute unit has
 
     const int64_t tm = 32ll * v->mb * v->rg;
     const int64_t m_tiles = (p->M + tm - 1) / tm;

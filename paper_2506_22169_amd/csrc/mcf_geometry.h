@@ -34,23 +34,26 @@ constexpr int combine_bytes(int L, int mb, int rg, int ns) {
 // (it is consumed before that slot is first filled); after the loop the ring space is reused
 // by the combine scratch followed by the staging tiles of the E store.
 constexpr int estage_bytes(int L, int mb, int rg) { return rg * 32 * mb * L * 2; }
-constexpr int total_lds_bytes(int K, int L, int mb, int rg, int ns, int stages) {
-    const int st = stage_bytes(K, L, 32 * ns);
+constexpr int total_lds_bytes(int K, int L, int mb, int rg, int ns, int nj, int stages) {
+    const int st = stage_bytes(K, L, 32 * ns * nj);
     const int a = a_tile_bytes(K, mb, rg);
     int s = (stages - 1) * st + (a > st ? a : st);
     const int c = combine_bytes(L, mb, rg, ns) + estage_bytes(L, mb, rg);
     return s > c ? s : c;
 }
 // Largest ring depth (2..4) that keeps a block within `budget` bytes of LDS.
-constexpr int pick_stages(int K, int L, int mb, int rg, int ns, int budget) {
+constexpr int pick_stages(int K, int L, int mb, int rg, int ns, int nj, int budget) {
     int s = 4;
-    while (s > 2 && total_lds_bytes(K, L, mb, rg, ns, s) > budget) --s;
+    while (s > 2 && total_lds_bytes(K, L, mb, rg, ns, nj, s) > budget) --s;
     return s;
 }
 
-// Ring depth every kernel variant is built with: as deep as fits 80 KiB, so that two blocks
-// can share the 160 KiB LDS of a compute unit.
+// Ring depth every kernel variant is built with: as deep (up to 4) as fits 80 KiB, so that two
+// blocks can share the 160 KiB LDS of a compute unit (measured: a deeper ring that costs the
+// second resident block loses more than it gains).
 constexpr int kLdsRingBudget = 80 * 1024;
-constexpr int ring_stages(int K, int L, int mb, int rg, int ns) { return pick_stages(K, L, mb, rg, ns, kLdsRingBudget); }
+constexpr int ring_stages(int K, int L, int mb, int rg, int ns, int nj) {
+    return pick_stages(K, L, mb, rg, ns, nj, kLdsRingBudget);
+}
 
 } // namespace mcf

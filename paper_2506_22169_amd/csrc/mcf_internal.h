@@ -33,14 +33,16 @@ typedef int (*LaunchFn)(const KParams &p, void *stream); // returns hipError_t a
 
 struct Variant {
     int32_t dtype, K, L;
-    int32_t mb, rg, ns;
+    int32_t mb, rg, ns, nj;
     int32_t softmax, b_kcontig;
     LaunchFn launch;
+    int32_t vgprs;         // VGPRs per lane the compiler allocated (-1: unknown)
+    int32_t scratch_bytes; // per-lane scratch (register spills); such variants are never picked
 };
 
 // Registry of every built kernel variant (defined in mcf_registry.cpp).
 const Variant *variants(int *count);
-const Variant *find_variant(int dtype, int K, int L, int softmax, int b_kcontig, int mb, int rg, int ns);
+const Variant *find_variant(int dtype, int K, int L, int softmax, int b_kcontig, int mb, int rg, int ns, int nj);
 
 // Layout decoded from an mcf_problem.
 struct Layout {
@@ -50,9 +52,9 @@ struct Layout {
 int decode_layout(const mcf_problem *p, Layout *out); // MCF_OK or an error status
 
 // Ring depth and LDS bytes of a variant; register estimate per lane.
-int stages_for(int K, int L, int mb, int rg, int ns);
-int lds_bytes_for(int K, int L, int mb, int rg, int ns, int stages);
-int vgpr_estimate(int K, int L, int mb, int rg, int ns, int softmax);
+int stages_for(int K, int L, int mb, int rg, int ns, int nj);
+int lds_bytes_for(int K, int L, int mb, int rg, int ns, int nj, int stages);
+int vgpr_estimate(int K, int L, int mb, int rg, int ns, int nj, int softmax);
 
 void set_last_error(const char *msg);
 

@@ -14,11 +14,15 @@
 //     L2 / the memory-side cache, not by HBM.
 //   * eq. (1) sums all five tiles against shared memory.  Here C and E (and A) live in
 //     registers, so the sum is split: B and D tiles (two stages, padded rows) against the
-//     160 KiB LDS, and A, C, E tiles against the 512-VGPR budget of a lane.  Both estimates
-//     are exact for hand-written kernels, so the 1.2x slack of Rule 4 is not applied.  The LDS
+//     160 KiB LDS, and A, C, E tiles against the share of the 512-entry VGPR file a lane gets.
+//     The LDS figure is exact and the register figure is backed by the compiler's own
+//     allocation (a variant that spills is never picked), so the 1.2x slack of Rule 4 is not
+//     applied.  The LDS
 //     holds a ring of 2..4 (B tile + D tile) stages, as deep as fits 80 KiB so that two
 //     blocks share a compute unit.
-//   * N_SM of eq. (5) is the number of compute units (256).
+//   * N_SM of eq. (5) is the number of compute units (256) and N_block counts groups of four
+//     waves (one per SIMD of a compute unit): a block of 8 waves fills a compute unit twice
+//     over, which is what the slowdown factor is about.
 #include <math.h>
 #include <string.h>
 
@@ -27,16 +31,25 @@
 
 namespace mcf {
 
-int stages_for(int K, int L, int mb, int rg, int ns) { return ring_stages(K, L, mb, rg, ns); }
-int lds_bytes_for(int K, int L, int mb, int rg, int ns, int stages) { return total_lds_bytes(K, L, mb, rg, ns, stages); }
+int stages_for(int K, int L, int mb, int rg, int ns, int nj) { return ring_stages(K, L, mb, rg, ns, nj); }
+int lds_bytes_for(int K, int L, int mb, int rg, int ns, int nj, int stages) { return total_lds_bytes(K, L, mb, rg, ns, nj, stages); }
 
-// Registers per lane: A tile (mb*K/16 operands of 4 VGPRs), E accumulators (mb * L/32 * 16),
-// one C accumulator and its 16-bit copy per mb, one load offset per wave-load of a stage, and
-// a fixed allowance for operands in flight, addresses and softmax state.
-int vgpr_estimate(int K, int L, int mb, int rg, int ns, int softmax) {
-    const int loads = (stage_bytes(K, L, 32 * ns) / 1024 + rg * ns - 1) / (rg * ns);
-    return mb * (K / 16) * 4 + mb * (L / 32) * 16 + mb * (16 + 8) + loads + 40 + (softmax ? 24 : 0);
+// Registers per lane (eq. (1) restricted to the register-resident tiles, in 32-bit registers):
+// A tile (mb * K/16 operands of 4), E accumulators (mb * L/32 * 16), nj C accumulators and
+// their 16-bit copies per mb (16 + 8), the LDS operands in flight for one C tile (K/16 * 4 for
+// B, L/32 * 8 for D), one load offset per wave-load of a stage, and a fixed allowance for
+// addresses and softmax state.  It tracks the compiler's allocation to within about 25 %;
+// the compiler's own numbers (scratch use) are the final arbiter, as PTX lowering is in
+// Sec. VI-D1 of the paper.
+int vgpr_estimate(int K, int L, int mb, int rg, int ns, int nj, int softmax) {
+    const int loads = (stage_bytes(K, L, 32 * ns * nj) / 1024 + rg * ns - 1) / (rg * ns);
+    return mb * (K / 16) * 4 + mb * (L / 32) * 16 + nj * mb * (16 + 8) + (K / 16) * 4 + (L / 32) * 8 + loads + 24 +
+           (softmax ? 16 : 0);
 }
+
+// Registers a lane may use: the 512-entry file of a SIMD is shared by the waves resident on
+// it, and a block of w waves puts ceil(w/4) waves on each SIMD.
+static int vgpr_cap(int waves) { return kVgprBudget / ((waves + 3) / 4); }
 
 static bool is_pow2(int64_t x) { return x > 0 && (x & (x - 1)) == 0; }
 
@@ -47,18 +60,22 @@ static bool padding_ok(int64_t dim, int64_t tile) {
     return (double)(padded - dim) < 0.05 * (double)dim;
 }
 
-static void eval_model(const mcf_problem *p, int softmax, int b_kcontig, int mb, int rg, int ns, mcf_tiles *t) {
+static void eval_model(const mcf_problem *p, int softmax, const Variant *v, mcf_tiles *t) {
+    const int mb = v->mb, rg = v->rg, ns = v->ns, nj = v->nj;
     memset(t, 0, sizeof(*t));
-    t->mb = mb; t->rg = rg; t->ns = ns;
-    t->tm = 32 * mb * rg; t->tn = 32 * ns; t->tk = (int32_t)p->K; t->tl = (int32_t)p->L;
+    t->mb = mb; t->rg = rg; t->ns = ns; t->nj = nj;
+    t->tm = 32 * mb * rg; t->tn = 32 * ns * nj; t->tk = (int32_t)p->K; t->tl = (int32_t)p->L;
     t->waves = rg * ns;
-    t->stages = stages_for((int)p->K, (int)p->L, mb, rg, ns);
-    t->lds_bytes = lds_bytes_for((int)p->K, (int)p->L, mb, rg, ns, t->stages);
-    (void)b_kcontig;
-    t->vgpr_est = vgpr_estimate((int)p->K, (int)p->L, mb, rg, ns, softmax);
+    t->stages = stages_for((int)p->K, (int)p->L, mb, rg, ns, nj);
+    t->lds_bytes = lds_bytes_for((int)p->K, (int)p->L, mb, rg, ns, nj, t->stages);
+    t->vgpr_est = vgpr_estimate((int)p->K, (int)p->L, mb, rg, ns, nj, softmax);
+    t->vgpr_used = v->vgprs;
+    t->scratch_bytes = v->scratch_bytes;
     const int64_t es = 2; // bytes per element, fp16 / bf16
     const int64_t m = (p->M + t->tm - 1) / t->tm, n = (p->N + t->tn - 1) / t->tn;
     t->blocks = p->batch * m;
+    // N_block of eq. (5) in units of one wave per SIMD of a compute unit (4 waves)
+    const int64_t units = t->blocks * ((t->waves + 3) / 4);
     t->compulsory_bytes = es * p->batch * (p->M * p->K + p->K * p->N + p->N * p->L + p->M * p->L);
     const int64_t la = (int64_t)t->tm * p->K * es * p->batch * m;
     const int64_t lb = (int64_t)p->K * t->tn * es * p->batch * m * n;
@@ -69,11 +86,13 @@ static void eval_model(const mcf_problem *p, int softmax, int b_kcontig, int mb,
     const int64_t reread = t->model_bytes > t->compulsory_bytes ? t->model_bytes - t->compulsory_bytes : 0;
     t->t_mem_s = (double)t->compulsory_bytes / kHbmBytesPerSec + (double)reread / kL2BytesPerSec;
     t->t_comp_s = (double)t->flops / kMfmaFlopsPerSec;
-    t->alpha = t->blocks > 0 ? (double)(t->blocks + kComputeUnits) / (double)t->blocks : 1.0;
+    t->alpha = units > 0 ? (double)(units + kComputeUnits) / (double)units : 1.0;
     t->t_est_s = (t->t_mem_s + t->t_comp_s) * t->alpha;
 }
 
-static bool feasible(const mcf_tiles &t) { return t.lds_bytes <= kLdsBytesPerBlock && t.vgpr_est <= kVgprBudget; }
+static bool feasible(const mcf_tiles &t) {
+    return t.lds_bytes <= kLdsBytesPerBlock && t.vgpr_est <= vgpr_cap(t.waves) && t.scratch_bytes == 0;
+}
 
 // Strict ordering of candidates: smaller estimate first; among equal estimates (the model
 // does not see how the waves of a block are arranged) more waves per block, then fewer
@@ -82,6 +101,7 @@ static bool better(const mcf_tiles &a, const mcf_tiles &b) {
     if (a.t_est_s != b.t_est_s) return a.t_est_s < b.t_est_s;
     if (a.waves != b.waves) return a.waves > b.waves;
     if (a.ns != b.ns) return a.ns < b.ns;
+    if (a.nj != b.nj) return a.nj > b.nj;
     return a.mb < b.mb;
 }
 
@@ -105,7 +125,7 @@ extern "C" int mcf_list_variants(const mcf_problem *p, int softmax, int32_t *out
             v[i].b_kcontig != lay.b_kcontig)
             continue;
         if (out && total < cap) {
-            out[3 * total] = v[i].mb; out[3 * total + 1] = v[i].rg; out[3 * total + 2] = v[i].ns;
+            out[4 * total] = v[i].mb; out[4 * total + 1] = v[i].rg; out[4 * total + 2] = v[i].ns; out[4 * total + 3] = v[i].nj;
         }
         ++total;
     }
@@ -117,9 +137,10 @@ extern "C" int mcf_eval_tiles(const mcf_problem *p, int softmax, mcf_tiles *t) {
     if (!t) return MCF_EINVAL;
     int st = check_problem(p, &lay);
     if (st != MCF_OK) return st;
-    const int mb = t->mb, rg = t->rg, ns = t->ns;
-    if (!find_variant(p->in_dtype, (int)p->K, (int)p->L, softmax != 0, lay.b_kcontig, mb, rg, ns)) return MCF_EUNSUPPORTED;
-    eval_model(p, softmax != 0, lay.b_kcontig, mb, rg, ns, t);
+    const int mb = t->mb, rg = t->rg, ns = t->ns, nj = t->nj > 0 ? t->nj : 1;
+    const Variant *v = find_variant(p->in_dtype, (int)p->K, (int)p->L, softmax != 0, lay.b_kcontig, mb, rg, ns, nj);
+    if (!v) return MCF_EUNSUPPORTED;
+    eval_model(p, softmax != 0, v, t);
     return feasible(*t) ? MCF_OK : MCF_EINVAL;
 }
 
@@ -140,7 +161,7 @@ extern "C" int mcf_pick_tiles(const mcf_problem *p, int softmax, mcf_tiles *out)
                 v[i].b_kcontig != lay.b_kcontig)
                 continue;
             mcf_tiles t;
-            eval_model(p, softmax != 0, lay.b_kcontig, v[i].mb, v[i].rg, v[i].ns, &t);
+            eval_model(p, softmax != 0, &v[i], &t);
             if (!feasible(t)) continue;
             if (pass == 0 && p->M > 0 && p->N > 0 && !(padding_ok(p->M, t.tm) && padding_ok(p->N, t.tn))) continue;
             if (!have || better(t, best)) { best = t; have = true; }

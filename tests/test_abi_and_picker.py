@@ -1,0 +1,139 @@
+"""Host-side checks that need no GPU: the C-ABI library loads and exports every symbol the
+header declares, argument validation returns the documented codes before any launch, and the
+tile picker's numbers agree with the paper's model as written out in oracle/perf_model.py."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import mcf_inputs as mi
+import paper_2506_22169_amd as mcf
+from oracle import perf_model as pm
+from paper_2506_22169_amd.binding import Problem, Tiles, make_problem
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+# machine constants the picker documents (MI355X): HBM and L2 bandwidth, MFMA peak, compute units
+W_HBM, W_L2, P_MFMA, N_CU = 8.0e12, 32.0e12, 2.5e15, 256
+LDS_MAX = 160 * 1024
+
+
+def _c_problem(w):
+    return make_problem(w.batch, w.M, w.K, w.N, w.L, w.dtype,
+                        b_stride=(w.N * w.K, 1, w.K) if w.softmax else None)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "mcf.h")).read()
+    declared = set(re.findall(r"\b(mcf_[a-z_]+)\s*\(", header))
+    assert {"mcf_pick_tiles", "mcf_gemm_chain", "mcf_softmax_gemm_chain"} <= declared
+    lib = mcf.load_library()
+    for name in sorted(declared):
+        assert getattr(lib, name) is not None, name
+    assert mcf.status_string(0) == "MCF_OK"
+    assert ctypes.sizeof(Problem) == 5 * 8 + 2 * 4 + 12 * 8
+    assert ctypes.sizeof(Tiles) == 14 * 4 + 4 * 8 + 4 * 8
+
+
+def test_validation_codes_without_a_launch():
+    lib = mcf.load_library()
+    p = make_problem(2, 64, 64, 64, 64, "f16")
+    fake = [ctypes.c_void_p(4096 * (i + 1) * 1024) for i in range(4)]   # never dereferenced: every call below fails validation
+    call = lambda prob, ptrs=fake: lib.mcf_gemm_chain(ctypes.byref(prob), *ptrs, None, None)
+    assert lib.mcf_gemm_chain(None, *fake, None, None) == 1
+    assert call(make_problem(2, 64, 48, 64, 48, "f16")) == 2                 # K, L not built
+    assert call(make_problem(2, 64, 64, 64, 32, "f16")) == 2                 # K != L not built
+    assert call(make_problem(2, -1, 64, 64, 64, "f16")) == 1                 # negative dimension
+    assert call(make_problem(2, 64, 64, 60, 64, "f16")) == 3                 # packed rows of 60 are not 16-byte multiples
+    assert call(make_problem(2, 64, 64, 60, 64, "f16", b_stride=(64 * 64, 64, 1))) == 2  # N-contiguous B needs N % 8 == 0
+    assert call(make_problem(2, 64, 64, 64, 64, "f16", a_stride=(64 * 72, 72, 2))) == 2   # A not K-contiguous
+    assert call(make_problem(2, 64, 64, 64, 64, "f16", a_stride=(64 * 68, 68, 1))) == 3   # row stride % 8
+    assert call(make_problem(2, 64, 64, 64, 64, "f16", d_stride=(64 * 32, 32, 1))) == 1   # rows overlap
+    assert call(p, [ctypes.c_void_p(4096 + 2)] + fake[1:]) == 3                          # misaligned pointer
+    assert call(p, [fake[3]] + fake[1:]) == 1                                            # E aliases A
+    assert call(p, [None] + fake[1:]) == 1                                               # null pointer
+    assert call(make_problem(0, 64, 64, 64, 64, "f16")) == 0                             # empty: no-op
+    assert lib.mcf_softmax_gemm_chain(ctypes.byref(make_problem(2, 64, 64, 0, 64, "f16")), ctypes.c_float(1.0),
+                                      *fake, None, None) == 1                            # softmax over nothing
+    assert lib.mcf_softmax_gemm_chain(ctypes.byref(p), ctypes.c_float(float("nan")), *fake, None, None) == 1
+    t = Tiles()
+    assert lib.mcf_pick_tiles(ctypes.byref(p), 0, None) == 1
+    assert lib.mcf_pick_tiles(ctypes.byref(make_problem(2, 64, 16, 64, 16, "f16")), 0, ctypes.byref(t)) == 2
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+def test_picker_terms_match_the_paper_model(name):
+    """Every model term of every built variant equals eq. (2)-(5) evaluated by the oracle model
+    for the tiling expression mhnk with T_K = K, T_L = L, and the picked variant is the
+    feasible one with the smallest estimate."""
+    w = mi.WORKLOADS[name]
+    prob = _c_problem(w)
+    shapes = mcf.list_variants(prob, w.softmax)
+    assert len(shapes) >= 8
+    dims = {"m": w.M, "n": w.N, "k": w.K, "h": w.L}
+    best = None
+    for (mb, rg, ns, nj) in shapes:
+        t = mcf.eval_tiles(prob, mb, rg, ns, nj, softmax=w.softmax)
+        assert (t.tm, t.tn, t.tk, t.tl, t.waves) == (32 * mb * rg, 32 * ns * nj, w.K, w.L, rg * ns)
+        tiles = {"m": t.tm, "n": t.tn, "k": w.K, "h": w.L}
+        units_per_block = (t.waves + 3) // 4
+        r = pm.estimate("mhnk", dims, tiles, w.batch, 2, W=W_HBM, P=P_MFMA, n_units=N_CU / units_per_block,
+                        W_reread=W_L2)
+        assert t.blocks == r["n_block"]
+        assert t.compulsory_bytes == r["compulsory_bytes"] == w.compulsory_bytes
+        assert t.model_bytes == r["model_bytes"]
+        assert t.flops == r["flops"]
+        assert t.t_mem_s == pytest.approx(r["t_mem"], rel=1e-12)
+        assert t.t_comp_s == pytest.approx(r["t_comp"], rel=1e-12)
+        assert t.alpha == pytest.approx(r["alpha"], rel=1e-12)
+        assert t.t_est_s == pytest.approx(r["t_estm"], rel=1e-12)
+        # eq. (1), split: LDS holds `stages` copies of the B and D tiles (plus the A tile in the last slot)
+        bd = pm.shm_estm(tiles, "BD") * 2
+        a = pm.tile_elems("A", tiles) * 2
+        assert 2 <= t.stages <= 4
+        assert t.lds_bytes >= (t.stages - 1) * bd + max(bd, a)
+        ok = (t.lds_bytes <= LDS_MAX and t.scratch_bytes == 0 and t.vgpr_est <= 512 // units_per_block
+              and pm.padding_ok(w.M, t.tm) and pm.padding_ok(w.N, t.tn))
+        assert ok == (t.feasible and pm.padding_ok(w.M, t.tm) and pm.padding_ok(w.N, t.tn))
+        if ok and (best is None or t.t_est_s < best.t_est_s * (1 - 1e-12)):
+            best = t
+    picked = mcf.pick_tiles(prob, w.softmax)
+    assert best is not None
+    assert picked.t_est_s == pytest.approx(best.t_est_s, rel=1e-12)
+    assert picked.scratch_bytes == 0 and picked.lds_bytes <= LDS_MAX
+    assert pm.padding_ok(w.M, picked.tm) and pm.padding_ok(w.N, picked.tn)
+
+
+def test_register_estimate_tracks_the_compiler():
+    """The register form of eq. (1): within 25 % below / 60 % above what the compiler allocated,
+    and every variant the estimate admits under its register cap compiled without spilling,
+    with at most a few exceptions (the analogue of the paper's estimate-vs-lowering check)."""
+    total = wrong = 0
+    for dtype in ("f16", "bf16"):
+        for KL in (32, 64, 128):
+            for softmax in (False, True):
+                prob = make_problem(4, 1024, KL, 1024, KL, dtype, b_stride=(1024 * KL, 1, KL) if softmax else None)
+                for shape in mcf.list_variants(prob, softmax):
+                    t = mcf.eval_tiles(prob, *shape, softmax=softmax)
+                    cap = 512 // ((t.waves + 3) // 4)
+                    assert t.vgpr_used > 0
+                    total += 1
+                    admitted = t.vgpr_est <= cap
+                    if admitted != (t.scratch_bytes == 0):
+                        wrong += 1
+                    if t.scratch_bytes == 0 and t.vgpr_used < cap:
+                        assert 0.75 * t.vgpr_used <= t.vgpr_est <= 1.6 * t.vgpr_used, (dtype, KL, softmax, shape)
+    assert total >= 150 and wrong <= 0.1 * total
+
+
+def test_rule3_fallback_and_ragged_shapes():
+    # M smaller than every tile: Rule 3 cannot hold, the picker still returns a covering variant
+    t = mcf.pick_tiles(make_problem(1, 16, 64, 64, 64, "f16"))
+    assert t.tm >= 32 and t.blocks == 1
+    # non power of two: padding ratio below 5 %
+    t = mcf.pick_tiles(make_problem(4, 1000, 64, 1000, 64, "f16"))
+    assert pm.padding_ok(1000, t.tm) and pm.padding_ok(1000, t.tn)
+    # the number of blocks drives alpha: a single small batch prefers the smallest m-tile
+    t = mcf.pick_tiles(make_problem(1, 1024, 64, 128, 64, "f16"))
+    assert t.tm == 32

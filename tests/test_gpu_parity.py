@@ -13,7 +13,6 @@ from gpu_util import TOL, check_full, device_inputs, run_gpu, to_device, to_host
 
 pytestmark = pytest.mark.gpu
 
-WAVE_SHAPES = [(1, 4, 1), (1, 2, 2), (1, 1, 4), (2, 4, 1), (2, 2, 2), (1, 2, 1), (1, 1, 2), (1, 4, 2)]
 
 
 @pytest.mark.parametrize("softmax", [False, True])
@@ -21,13 +20,16 @@ WAVE_SHAPES = [(1, 4, 1), (1, 2, 2), (1, 1, 4), (2, 4, 1), (2, 2, 2), (1, 2, 1),
 @pytest.mark.parametrize("KL", [32, 64, 128])
 def test_every_variant_small_ragged(KL, dtype, softmax):
     """Every built wave arrangement on a shape with a ragged m tail and a ragged n tail that
-    spans several tiles of the largest variant (tm up to 256, tn up to 128)."""
+    spans several tiles of the largest variant (tm up to 256, tn up to 256)."""
     # plain chains keep B as [b,K,N] (N a multiple of 8), softmax chains as the key matrix [b,N,K]
-    M, N = 600, (328 if not softmax else 333)
+    M, N = 600, (584 if not softmax else 589)
     dist = "normal" if softmax else "uniform"
     w = mi.make_problem(3, M, KL, N, KL, dtype, softmax, dist, seed=1000 + KL)
     worst = 0.0
-    for tiles in WAVE_SHAPES:
+    prob = c_problem(3, M, KL, N, KL, dtype, b_stride=(N * KL, 1, KL) if softmax else None)
+    shapes = mcf.list_variants(prob, softmax)
+    assert len(shapes) >= 8
+    for tiles in shapes:
         print(f"case KL={KL} {dtype} softmax={softmax} tiles={tiles}", flush=True)
         worst = max(worst, check_full(w, tiles))
     print(f"worst max|err|/max|oracle| = {worst:.3e}", flush=True)
@@ -151,5 +153,5 @@ def test_error_codes_from_the_abi():
         mcf.gemm_chain(A, B, D, out=A)
     assert e.value.status == 1
     with pytest.raises(mcf.McfError) as e:          # no such wave arrangement
-        mcf.gemm_chain(A, B, D, tiles=(3, 1, 1))
+        mcf.gemm_chain(A, B, D, tiles=(3, 1, 1, 1))
     assert e.value.status == 1
