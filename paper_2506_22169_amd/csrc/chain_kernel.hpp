@@ -92,20 +92,6 @@ static __device__ __forceinline__ i16x4 lds_read_tr(const lds_u8 *p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4 *)p);
 }
 
-// Direct global -> LDS load of 16 bytes per lane: lane i's piece lands at lds_addr + 16*i.
-// lds_addr (a byte address in LDS) and base are wave-uniform; voff is the lane's byte offset
-// from base.  Written as inline assembly so that the compiler does not serialise later LDS
-// reads behind every outstanding load; completion is awaited with wait_vm<>().
-static __device__ __forceinline__ void dma16(unsigned lds_addr, unsigned voff, const void *base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :
-                 : "s"(lds_addr), "v"(voff), "s"(base)
-                 : "memory", "m0");
-}
-template <int N> static __device__ __forceinline__ void wait_vm() {
-    static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
 // Marks a wave-uniform value as such for the register allocator (it must live in SGPRs to
 // feed M0 / the scalar base of a direct-to-LDS load).
 static __device__ __forceinline__ unsigned uniform(unsigned v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -114,6 +100,20 @@ static __device__ __forceinline__ const void *uniform(const void *q) {
     return (const void *)(((uint64_t)uniform((unsigned)(b >> 32)) << 32) | uniform((unsigned)b));
 }
 
+// Direct global -> LDS load of 16 bytes per lane: lane i's piece lands at lds_addr + 16*i.
+// lds_addr (a byte address in LDS) and base are wave-uniform; voff is the lane's byte offset
+// from base.  Written as inline assembly so that the compiler does not serialise later LDS
+// reads behind every outstanding load; completion is awaited with wait_vm<>().
+static __device__ __forceinline__ void dma16(unsigned lds_addr, unsigned voff, const void *base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(uniform(lds_addr)), "v"(voff), "s"(uniform(base))
+                 : "memory", "m0");
+}
+template <int N> static __device__ __forceinline__ void wait_vm() {
+    static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool BKC>
 __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     using M_ = Mfma<T>;
@@ -123,7 +123,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     constexpr int TN = 32 * NS * NJ;     // columns per n-iteration
     constexpr int KS = KD / 16;          // MFMA k-steps of GEMM 1
     constexpr int HB = LD / 32;          // 32-wide h blocks of GEMM 2
-    constexpr int S = ring_stages(KD, LD, MB, RG, NS, NJ); // depth of the LDS ring
+    constexpr int S = ring_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX); // depth of the LDS ring
     constexpr int RBA = 2 * KD;                  // row bytes of the A tile (rows m)
     constexpr int RBB = BKC ? 2 * KD : 2 * TN;   // row bytes of the B tile (rows n / rows k)
     constexpr int RBD = 2 * LD;                  // row bytes of the D tile (rows n)
@@ -307,128 +307,138 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     }
 
     MCF_TRACE_POINT(4);
-    int stage_c = 0;     // ring slot of the tile being consumed
-    int stage_l = S - 1; // ring slot the next issued tile goes to
-    for (int it = 0; it < n_iters; ++it) {
-        // Tiles it .. min(it+S-2, n_iters-1) are in flight.  Retire tile `it`: in the steady
-        // state S-2 younger groups may stay in flight, near the end simply drain.
-        if (n_iters - it >= S - 1) wait_vm<(S - 2) * P>();
-        else wait_vm<0>();
-        MCF_TRACE_POINT(8 + 3 * (it & 7));
-        if (!(MCF_ABLATE & 16)) __syncthreads(); // tile `it` is complete for every wave; the slot of tile it-1 is free
-        if (it + S - 1 < n_iters && !(MCF_ABLATE & 32)) {
-            issue_tile(it + S - 1, stage_l);
-            stage_l = stage_l + 1 == S ? 0 : stage_l + 1;
+    // LDS -> register operand fetches (sT = base of the ring slot holding the tile).
+    auto load_b = [&](const lds_u8 *sT, int j, int ks) -> v8 {
+        if (MCF_ABLATE & 1) return a[0][ks];
+        if (BKC) {
+            return __builtin_bit_cast(v8, *(const lds_u32x4 *)(sT + ((b_off ^ (32 * ks)) + 32 * j * RBB)));
+        } else {
+            const lds_u8 *src = sT + ((b_off ^ (64 * j)) + (16 * ks) * RBB);
+            i16x4 lo = lds_read_tr(src);
+            i16x4 hi = lds_read_tr(src + 4 * RBB);
+            return __builtin_bit_cast(v8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         }
+    };
+    auto load_d = [&](const lds_u8 *sT, int j, int hb, int qp) -> v8 {
+        if (MCF_ABLATE & 1) return a[0][(2 * hb + qp) % KS];
+        const lds_u8 *src = sT + ((d_off ^ (64 * hb)) + (32 * j + 16 * qp) * RBD);
+        i16x4 lo = lds_read_tr(src);
+        i16x4 hi = lds_read_tr(src + 8 * RBD);
+        return __builtin_bit_cast(v8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    // Operands are requested PF MFMA steps ahead of their use so that the LDS latency hides
+    // behind the MFMAs already issued; the scheduling barriers keep every LDS read and MFMA
+    // in the step it was written in (plain VALU / SALU work may still move across).
+    constexpr int PF = 2;
 
-        MCF_TRACE_POINT(9 + 3 * (it & 7));
-        const lds_u8 *sT = smem + stage_c * STAGE;
-        stage_c = stage_c + 1 == S ? 0 : stage_c + 1;
-        const int n0 = it * TN + wn * (32 * NJ); // first column of this wave's 32*NJ-wide slice
-
-        if (n0 < N) {
-            // ---- C_C: C^T[n][m] = sum_k B^T[n][k] A^T[k][m], NJ independent 32-column slices ----
-            f32x16 accC[NJ][MB];
-#pragma unroll
-            for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) accC[j][mb][r] = 0.f;
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    v8 bop;
-                    if (MCF_ABLATE & 1) {
-                        bop = a[0][ks];
-                    } else if (BKC) {
-                        bop = __builtin_bit_cast(v8, *(const lds_u32x4 *)(sT + ((b_off ^ (32 * ks)) + 32 * j * RBB)));
-                    } else {
-                        const lds_u8 *src = sT + ((b_off ^ (64 * j)) + (16 * ks) * RBB);
-                        i16x4 lo = lds_read_tr(src);
-                        i16x4 hi = lds_read_tr(src + 4 * RBB);
-                        i16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                        bop = __builtin_bit_cast(v8, both);
-                    }
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) {
-                        if (MCF_ABLATE & 2) accC[j][mb][ks] += (float)bop[0] * (float)a[mb][ks][1];
-                        else accC[j][mb] = M_::run(bop, a[mb][ks], accC[j][mb]);
-                    }
-                }
+    {
+        constexpr int T1 = NJ * KS;     // MFMA steps of GEMM 1 (each feeds MB MFMAs)
+        constexpr int T2 = NJ * HB * 2; // MFMA steps of GEMM 2
+        int stage_c = 0;     // ring slot of the tile being consumed
+        int stage_l = S - 1; // ring slot the next issued tile goes to
+        for (int it = 0; it < n_iters; ++it) {
+            // Tiles it .. min(it+S-2, n_iters-1) are in flight.  Retire tile `it`: in the steady
+            // state S-2 younger groups may stay in flight, near the end simply drain.
+            if (n_iters - it >= S - 1) wait_vm<(S - 2) * P>();
+            else wait_vm<0>();
+            MCF_TRACE_POINT(8 + 3 * (it & 7));
+            if (!(MCF_ABLATE & 16)) __syncthreads(); // tile `it` is complete for every wave; the slot of tile it-1 is free
+            if (it + S - 1 < n_iters && !(MCF_ABLATE & 32)) {
+                issue_tile(it + S - 1, stage_l);
+                stage_l = stage_l + 1 == S ? 0 : stage_l + 1;
             }
 
-            // ---- softmax (online max / sum over n-tiles) and conversion to 16 bit -----------
-            // Lane (c,g) holds, for row m = c, the columns n = n0 + 32j + 8(r/4) + 4g + r%4.
-            v8 pop[NJ][MB][2];
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                if (n0 + 32 * NJ > N) { // ragged last tile: columns past N contribute nothing
-#pragma unroll
-                    for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            if (n0 + 32 * j + 8 * (r / 4) + 4 * g + (r % 4) >= N) accC[j][mb][r] = SOFTMAX ? -INFINITY : 0.f;
-                }
-                if (SOFTMAX) {
-                    float mx = accC[0][mb][0];
-#pragma unroll
-                    for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, accC[j][mb][r]);
-                    mx = xhalf_max(mx);
-                    const float m_new = fmaxf(m_run[mb], mx);
-                    const float corr = __builtin_amdgcn_exp2f((m_run[mb] - m_new) * c1);
-                    const float mneg = -m_new * c1;
-                    float sum = 0.f;
-#pragma unroll
-                    for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            accC[j][mb][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(accC[j][mb][r], c1, mneg));
-                            sum += accC[j][mb][r];
-                        }
-                    l_run[mb] = l_run[mb] * corr + sum;
-                    m_run[mb] = m_new;
-                    if (__builtin_amdgcn_ballot_w64(corr != 1.0f)) {
-#pragma unroll
-                        for (int hb = 0; hb < HB; ++hb)
-#pragma unroll
-                            for (int r = 0; r < 16; ++r) accE[mb][hb][r] *= corr;
-                    }
-                }
+            MCF_TRACE_POINT(9 + 3 * (it & 7));
+            const lds_u8 *sT = smem + stage_c * STAGE;
+            stage_c = stage_c + 1 == S ? 0 : stage_c + 1;
+            const int n0 = it * TN + wn * (32 * NJ); // first column of this wave's 32*NJ-wide slice
+
+            if (n0 < N) {
+                // ---- C_C: C^T[n][m] = sum_k B^T[n][k] A^T[k][m], NJ independent 32-column slices
+                f32x16 accC[NJ][MB];
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                    for (int qp = 0; qp < 2; ++qp)
+                    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) pop[j][mb][qp][e] = (T)accC[j][mb][8 * qp + e];
-            }
+                        for (int r = 0; r < 16; ++r) accC[j][mb][r] = 0.f;
+                v8 bop[T1];
+#pragma unroll
+                for (int t = 0; t < PF && t < T1; ++t) bop[t] = load_b(sT, t / KS, t % KS);
+#pragma unroll
+                for (int t = 0; t < T1; ++t) {
+                    const int j = t / KS, ks = t % KS;
+                    if (t + PF < T1) bop[t + PF] = load_b(sT, (t + PF) / KS, (t + PF) % KS);
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) {
+                        if (MCF_ABLATE & 2) accC[j][mb][ks] += (float)bop[t][0] * (float)a[mb][ks][1];
+                        else accC[j][mb] = M_::run(bop[t], a[mb][ks], accC[j][mb]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0x406);
+                }
+                // first D operands: their LDS latency overlaps the conversion below
+                v8 dop[T2];
+#pragma unroll
+                for (int t = 0; t < PF && t < T2; ++t) dop[t] = load_d(sT, t / (2 * HB), (t / 2) % HB, t % 2);
 
-            // ---- C_E: E^T[h][m] += sum_n D^T[h][n] P^T[n][m] --------------------------------
+                // ---- softmax (online max / sum over n-tiles) and conversion to 16 bit: lane (c,g)
+                //      holds, for row m = c, the columns n = n0 + 32j + 8(r/4) + 4g + r%4
+                v8 pop[NJ][MB][2];
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) {
+                for (int mb = 0; mb < MB; ++mb) {
+                    if (n0 + 32 * NJ > N) { // ragged last tile: columns past N contribute nothing
 #pragma unroll
-                for (int hb = 0; hb < HB; ++hb) {
+                        for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                    for (int qp = 0; qp < 2; ++qp) {
-                        const lds_u8 *src = sT + ((d_off ^ (64 * hb)) + (32 * j + 16 * qp) * RBD);
-                        v8 dop;
-                        if (MCF_ABLATE & 1) {
-                            dop = a[0][(2 * hb + qp) % KS];
-                        } else {
-                            i16x4 lo = lds_read_tr(src);
-                            i16x4 hi = lds_read_tr(src + 8 * RBD);
-                            i16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                            dop = __builtin_bit_cast(v8, both);
-                        }
+                            for (int r = 0; r < 16; ++r)
+                                if (n0 + 32 * j + 8 * (r / 4) + 4 * g + (r % 4) >= N) accC[j][mb][r] = SOFTMAX ? -INFINITY : 0.f;
+                    }
+                    if (SOFTMAX) {
+                        float mx = accC[0][mb][0];
 #pragma unroll
-                        for (int mb = 0; mb < MB; ++mb) {
-                            if (MCF_ABLATE & 2) accE[mb][hb][qp] += (float)dop[0] * (float)pop[j][mb][qp][1];
-                            else accE[mb][hb] = M_::run(dop, pop[j][mb][qp], accE[mb][hb]);
+                        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, accC[j][mb][r]);
+                        mx = xhalf_max(mx);
+                        const float m_new = fmaxf(m_run[mb], mx);
+                        const float corr = __builtin_amdgcn_exp2f((m_run[mb] - m_new) * c1);
+                        const float mneg = -m_new * c1;
+                        float sum = 0.f;
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                accC[j][mb][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(accC[j][mb][r], c1, mneg));
+                                sum += accC[j][mb][r];
+                            }
+                        l_run[mb] = l_run[mb] * corr + sum;
+                        m_run[mb] = m_new;
+                        if (__builtin_amdgcn_ballot_w64(corr != 1.0f)) {
+#pragma unroll
+                            for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+                                for (int r = 0; r < 16; ++r) accE[mb][hb][r] *= corr;
                         }
                     }
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                        for (int qp = 0; qp < 2; ++qp)
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) pop[j][mb][qp][e] = (T)accC[j][mb][8 * qp + e];
+                }
+
+                // ---- C_E: E^T[h][m] += sum_n D^T[h][n] P^T[n][m] ----------------------------
+#pragma unroll
+                for (int t = 0; t < T2; ++t) {
+                    const int j = t / (2 * HB), hb = (t / 2) % HB, qp = t % 2;
+                    if (t + PF < T2) dop[t + PF] = load_d(sT, (t + PF) / (2 * HB), ((t + PF) / 2) % HB, (t + PF) % 2);
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) {
+                        if (MCF_ABLATE & 2) accE[mb][hb][qp] += (float)dop[t][0] * (float)pop[j][mb][qp][1];
+                        else accE[mb][hb] = M_::run(dop[t], pop[j][mb][qp], accE[mb][hb]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0x406);
                 }
             }
         }
@@ -443,47 +453,77 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
 
     __syncthreads(); // every wave is done reading the ring: its space is reused below
 
-    // ---- combine the ns partial results of a row-group (waves wn > 0 -> wave wn == 0) -------
+    // ---- combine the ns partial results of a row-group -----------------------------------
+    // The MB*HB accumulator blocks (32 rows x 32 columns of E each) of a row-group are dealt
+    // out to its ns waves in contiguous runs of BPW; every wave parks the blocks it does not
+    // own (and its softmax state) in LDS, then reduces and stores the blocks it owns, so the
+    // reduction and the store are spread over all waves.  Partial results are summed in wave
+    // order, which makes the result independent of timing.
+    constexpr int NBLK = MB * HB;
+    constexpr int BPW = blocks_per_wave(LD, MB, NS);
+    const int blk0 = wn * BPW; // this wave owns blocks [blk0, blk0 + BPW) that exist
     if (NS > 1 && !(MCF_ABLATE & 4)) {
-        constexpr int PER_MB = HB * 16 + 2; // floats per lane per mb
-        lds_f32 *scratch = (lds_f32 *)smem;
-        if (wn > 0) {
-            lds_f32 *dst = scratch + ((wr * (NS - 1) + (wn - 1)) * MB) * PER_MB * 64 + lane;
+        constexpr int PARK = parked_blocks(LD, MB, NS); // blocks a wave parks (those it does not own)
+        constexpr int PER_W = PARK * 16 + 2 * MB;       // floats per lane per wave
+        lds_f32 *scr = (lds_f32 *)smem + (wr * NS) * PER_W * 64 + lane;
+        lds_f32 *mine = scr + wn * PER_W * 64;
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
+        for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
-                for (int hb = 0; hb < HB; ++hb)
+            for (int hb = 0; hb < HB; ++hb) {
+                const int blk = mb * HB + hb;
+                if (blk < blk0 || blk >= blk0 + BPW) {
+                    const int pidx = blk >= blk0 + BPW ? blk - BPW : blk; // skip the run this wave owns
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) dst[(mb * PER_MB + hb * 16 + r) * 64] = accE[mb][hb][r];
-                dst[(mb * PER_MB + HB * 16) * 64] = m_run[mb];
-                dst[(mb * PER_MB + HB * 16 + 1) * 64] = l_run[mb];
+                    for (int r = 0; r < 16; ++r) mine[(pidx * 16 + r) * 64] = accE[mb][hb][r];
+                }
+            }
+            if (SOFTMAX) {
+                mine[(PARK * 16 + 2 * mb) * 64] = m_run[mb];
+                mine[(PARK * 16 + 2 * mb + 1) * 64] = l_run[mb];
             }
         }
         __syncthreads();
-        if (wn == 0) {
 #pragma unroll
-            for (int w = 1; w < NS; ++w) {
-                const lds_f32 *src = scratch + ((wr * (NS - 1) + (w - 1)) * MB) * PER_MB * 64 + lane;
+        for (int mb = 0; mb < MB; ++mb) {
+            // blocks mb*HB .. mb*HB+HB-1: does this wave own one of them?
+            if (blk0 < (mb + 1) * HB && blk0 + BPW > mb * HB) {
+                float f[NS];
+                if (SOFTMAX) {
+                    float mw[NS], lw[NS];
+                    float m_all = -INFINITY;
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    float f_own = 1.f, f_oth = 1.f;
-                    if (SOFTMAX) {
-                        const float m_o = src[(mb * PER_MB + HB * 16) * 64];
-                        const float l_o = src[(mb * PER_MB + HB * 16 + 1) * 64];
-                        const float m_new = fmaxf(m_run[mb], m_o);
-                        // a wave that saw no column has m = -inf, l = 0 and a zero accumulator
-                        f_own = (m_run[mb] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_run[mb] - m_new) * c1);
-                        f_oth = (m_o == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_o - m_new) * c1);
-                        l_run[mb] = l_run[mb] * f_own + l_o * f_oth;
-                        m_run[mb] = m_new;
+                    for (int w = 0; w < NS; ++w) {
+                        mw[w] = scr[(w * PER_W + PARK * 16 + 2 * mb) * 64];
+                        lw[w] = scr[(w * PER_W + PARK * 16 + 2 * mb + 1) * 64];
+                        m_all = fmaxf(m_all, mw[w]);
                     }
+                    float l_all = 0.f;
 #pragma unroll
-                    for (int hb = 0; hb < HB; ++hb)
+                    for (int w = 0; w < NS; ++w) {
+                        // a wave that saw no column has m = -inf, l = 0 and a zero accumulator
+                        f[w] = (mw[w] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((mw[w] - m_all) * c1);
+                        l_all += f[w] * lw[w];
+                    }
+                    l_run[mb] = l_all;
+                }
+#pragma unroll
+                for (int hb = 0; hb < HB; ++hb) {
+                    const int blk = mb * HB + hb;
+                    if (blk >= blk0 && blk < blk0 + BPW) {
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
-                            const float o = src[(mb * PER_MB + hb * 16 + r) * 64];
-                            accE[mb][hb][r] = SOFTMAX ? accE[mb][hb][r] * f_own + o * f_oth : accE[mb][hb][r] + o;
+                            float acc = 0.f;
+#pragma unroll
+                            for (int w = 0; w < NS; ++w) {
+                                // where wave w parked this block (w does not own it when w != wn)
+                                const int pidx = blk >= (w + 1) * BPW ? blk - BPW : blk;
+                                const float part = (w == wn) ? accE[mb][hb][r] : scr[(w * PER_W + pidx * 16 + r) * 64];
+                                acc += SOFTMAX ? f[w] * part : part;
+                            }
+                            accE[mb][hb][r] = acc;
                         }
+                    }
                 }
             }
         }
@@ -491,38 +531,48 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
 
     MCF_TRACE_POINT(6);
     // ---- S_E: E tile -> global ------------------------------------------------------------
-    // Lane (c,g) holds E[row c][32hb + 16g + 0..15].  The wave's 32*MB x L tile is staged in
-    // LDS (swizzled) and read back so that consecutive lanes store consecutive 16-byte pieces
-    // of a row: every store instruction writes whole 2L-byte rows.
-    if (NS == 1 || wn == 0) {
-        lds_u8 *es = smem + combine_bytes(LD, MB, RG, NS) + wr * (32 * MB * RBE);
+    // Lane (c,g) holds E[row c][32hb + 16g + 0..15] of the blocks its wave owns.  They are
+    // staged in LDS (swizzled) and read back so that consecutive lanes store consecutive
+    // 16-byte pieces of a row: a store instruction writes whole row segments (whole rows when
+    // the wave owns all h blocks of its rows).
+    if (blk0 < NBLK) {
+        constexpr int HPW = BPW < HB ? BPW : HB;    // h blocks per owned row set
+        constexpr int MPW = BPW < HB ? 1 : BPW / HB; // row sets (of 32 rows) owned
+        constexpr int RBS = HPW * 64;                // staged row bytes
+        const int mb0 = blk0 / HB, h0 = blk0 % HB;
+        lds_u8 *es = smem + combine_bytes(LD, MB, RG, NS) + wave * (BPW * 2048);
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-            const int row = 32 * mb + c;
             const float inv = SOFTMAX ? 1.0f / l_run[mb] : 1.0f;
-            const int sw = swz_b128(RBE, row);
 #pragma unroll
             for (int hb = 0; hb < HB; ++hb) {
-                v8 lo, hi;
+                const int blk = mb * HB + hb;
+                if (blk >= blk0 && blk < blk0 + BPW) {
+                    const int row = 32 * (mb - mb0) + c;
+                    const int sw = swz_b128(RBS, row);
+                    v8 lo, hi;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    lo[e] = (T)(accE[mb][hb][e] * inv);
-                    hi[e] = (T)(accE[mb][hb][8 + e] * inv);
+                    for (int e = 0; e < 8; ++e) {
+                        lo[e] = (T)(accE[mb][hb][e] * inv);
+                        hi[e] = (T)(accE[mb][hb][8 + e] * inv);
+                    }
+                    const int ch = 4 * (hb - h0) + 2 * g;
+                    *(lds_u32x4 *)(es + row * RBS + 16 * (ch ^ sw)) = __builtin_bit_cast(u32x4, lo);
+                    *(lds_u32x4 *)(es + row * RBS + 16 * ((ch + 1) ^ sw)) = __builtin_bit_cast(u32x4, hi);
                 }
-                *(lds_u32x4 *)(es + row * RBE + 16 * ((4 * hb + 2 * g) ^ sw)) = __builtin_bit_cast(u32x4, lo);
-                *(lds_u32x4 *)(es + row * RBE + 16 * ((4 * hb + 2 * g + 1) ^ sw)) = __builtin_bit_cast(u32x4, hi);
             }
         }
-        constexpr int CPR = RBE / 16;               // 16-byte pieces per row
-        constexpr int PASSES = 32 * MB * CPR / 64;  // wave-wide stores for the tile
-        const int rbase = mrow0 + wr * (32 * MB);
+        constexpr int CPR = RBS / 16;               // 16-byte pieces per staged row
+        constexpr int PASSES = MPW * 32 * CPR / 64; // wave-wide stores
+        const int rbase = mrow0 + wr * (32 * MB) + 32 * mb0;
 #pragma unroll
         for (int ps = 0; ps < PASSES; ++ps) {
             const int slot = 64 * ps + lane;
             const int row = slot / CPR;
-            const int ch = (slot % CPR) ^ swz_b128(RBE, row);
+            const int ch = (slot % CPR) ^ swz_b128(RBS, row);
             const u32x4 v = *(const lds_u32x4 *)(es + 16 * slot);
-            if (rbase + row < M && (!(MCF_ABLATE & 8) || v[0] == 0x12345u)) *(u32x4 *)(Eg + (int64_t)(rbase + row) * se_r + 8 * ch) = v;
+            if (rbase + row < M && (!(MCF_ABLATE & 8) || v[0] == 0x12345u))
+                *(u32x4 *)(Eg + (int64_t)(rbase + row) * se_r + 32 * h0 + 8 * ch) = v;
         }
     }
     MCF_TRACE_POINT(7);
@@ -531,7 +581,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
 // Host-side launcher of one instantiation.
 template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool BKC>
 int launch_chain(const KParams &p, void *stream) {
-    constexpr int lds = total_lds_bytes(KD, LD, MB, RG, NS, NJ, ring_stages(KD, LD, MB, RG, NS, NJ));
+    constexpr int lds = total_lds_bytes(KD, LD, MB, RG, NS, NJ, ring_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX));
     auto kern = chain_kernel<T, KD, LD, MB, RG, NS, NJ, SOFTMAX, BKC>;
     static bool attr_done = false; // benign race: setting the attribute twice is harmless
     if (lds > 64 * 1024 && !attr_done) {
@@ -547,7 +597,7 @@ int launch_chain(const KParams &p, void *stream) {
 // (K, L): more LDS than a compute unit has.  Such kernels are not compiled at all.
 template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool BKC>
 constexpr LaunchFn launcher_or_null() {
-    if constexpr (total_lds_bytes(KD, LD, MB, RG, NS, NJ, ring_stages(KD, LD, MB, RG, NS, NJ)) <= kLdsBytesPerBlock)
+    if constexpr (total_lds_bytes(KD, LD, MB, RG, NS, NJ, ring_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX)) <= kLdsBytesPerBlock)
         return &launch_chain<T, KD, LD, MB, RG, NS, NJ, SOFTMAX, BKC>;
     else
         return nullptr;

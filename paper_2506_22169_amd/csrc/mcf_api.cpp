@@ -95,7 +95,7 @@ static int run(const mcf_problem *p, int softmax, float scale, const void *A, co
     }
     const Variant *v = find_variant(p->in_dtype, (int)p->K, (int)p->L, softmax, lay.b_kcontig, chosen.mb, chosen.rg, chosen.ns, chosen.nj > 0 ? chosen.nj : 1);
     if (!v) return tiles ? MCF_EINVAL : MCF_EUNSUPPORTED;
-    if (lds_bytes_for((int)p->K, (int)p->L, v->mb, v->rg, v->ns, v->nj, stages_for((int)p->K, (int)p->L, v->mb, v->rg, v->ns, v->nj)) >
+    if (lds_bytes_for((int)p->K, (int)p->L, v->mb, v->rg, v->ns, v->nj, stages_for((int)p->K, (int)p->L, v->mb, v->rg, v->ns, v->nj, softmax)) >
         kLdsBytesPerBlock)
         return MCF_EINVAL; // more LDS than a compute unit has
 

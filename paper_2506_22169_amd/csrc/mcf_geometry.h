@@ -25,20 +25,28 @@ constexpr int a_tile_bytes(int K, int mb, int rg) { return 32 * mb * rg * K * 2;
 constexpr int b_tile_bytes(int K, int tn) { return K * tn * 2; }
 constexpr int d_tile_bytes(int L, int tn) { return tn * L * 2; }
 constexpr int stage_bytes(int K, int L, int tn) { return b_tile_bytes(K, tn) + d_tile_bytes(L, tn); }
-// Scratch for the cross-wave combine when ns > 1: per row-group, (ns-1) waves park their E
-// accumulators (fp32) and softmax state.
-constexpr int combine_bytes(int L, int mb, int rg, int ns) {
-    return ns > 1 ? rg * (ns - 1) * mb * ((L / 32) * 16 + 2) * 64 * 4 : 0;
+// Cross-wave combine when ns > 1: the mb * L/32 accumulator blocks (32 x 32 of E, 16 fp32 per
+// lane) of a row-group are dealt out to its ns waves, BPW in a row; every wave parks the
+// blocks it does not own and its softmax state in LDS.
+constexpr int blocks_per_wave(int L, int mb, int ns) { return (mb * (L / 32) + ns - 1) / ns; }
+// Blocks a wave parks: all but the run it owns (waves beyond the last run own none).
+constexpr int parked_blocks(int L, int mb, int ns) {
+    const int n = mb * (L / 32);
+    return n >= ns ? n - blocks_per_wave(L, mb, ns) : n;
 }
+constexpr int combine_bytes(int L, int mb, int rg, int ns) {
+    return ns > 1 ? rg * ns * (parked_blocks(L, mb, ns) * 16 + 2 * mb) * 64 * 4 : 0;
+}
+// Staging tiles of the E store: 2 KiB (32 rows x 64 bytes) per owned block and wave.
+constexpr int estage_bytes(int L, int mb, int rg, int ns) { return rg * ns * blocks_per_wave(L, mb, ns) * 2048; }
 // `stages` ring buffers of one B + D tile each; the A tile is staged in the last ring slot
 // (it is consumed before that slot is first filled); after the loop the ring space is reused
 // by the combine scratch followed by the staging tiles of the E store.
-constexpr int estage_bytes(int L, int mb, int rg) { return rg * 32 * mb * L * 2; }
 constexpr int total_lds_bytes(int K, int L, int mb, int rg, int ns, int nj, int stages) {
     const int st = stage_bytes(K, L, 32 * ns * nj);
     const int a = a_tile_bytes(K, mb, rg);
     int s = (stages - 1) * st + (a > st ? a : st);
-    const int c = combine_bytes(L, mb, rg, ns) + estage_bytes(L, mb, rg);
+    const int c = combine_bytes(L, mb, rg, ns) + estage_bytes(L, mb, rg, ns);
     return s > c ? s : c;
 }
 // Largest ring depth (2..4) that keeps a block within `budget` bytes of LDS.
@@ -52,7 +60,7 @@ constexpr int pick_stages(int K, int L, int mb, int rg, int ns, int nj, int budg
 // blocks can share the 160 KiB LDS of a compute unit (measured: a deeper ring that costs the
 // second resident block loses more than it gains).
 constexpr int kLdsRingBudget = 80 * 1024;
-constexpr int ring_stages(int K, int L, int mb, int rg, int ns, int nj) {
+constexpr int ring_stages(int K, int L, int mb, int rg, int ns, int nj, bool /*softmax*/) {
     return pick_stages(K, L, mb, rg, ns, nj, kLdsRingBudget);
 }
 

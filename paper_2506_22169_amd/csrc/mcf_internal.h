@@ -10,7 +10,8 @@ namespace mcf {
 constexpr double kHbmBytesPerSec = 8.0e12;    // W: HBM3E peak
 constexpr double kL2BytesPerSec = 32.0e12;    // bandwidth charged to re-reads served by L2/MALL
 constexpr double kMfmaFlopsPerSec = 2.5e15;   // P: dense fp16/bf16 MFMA peak
-constexpr int kComputeUnits = 256;            // N_SM
+constexpr int kComputeUnits = 256;            // compute units
+constexpr int kWaveSlots = kComputeUnits * 4 * 2; // N_SM of eq. (5): two waves on each of the 4 SIMDs of a CU
 constexpr int kLdsBytesPerBlock = 160 * 1024; // Shm_max of Rule 4
 constexpr int kVgprBudget = 512;              // arch + accumulation VGPRs per lane at 1 wave/SIMD
 
@@ -52,7 +53,7 @@ struct Layout {
 int decode_layout(const mcf_problem *p, Layout *out); // MCF_OK or an error status
 
 // Ring depth and LDS bytes of a variant; register estimate per lane.
-int stages_for(int K, int L, int mb, int rg, int ns, int nj);
+int stages_for(int K, int L, int mb, int rg, int ns, int nj, int softmax);
 int lds_bytes_for(int K, int L, int mb, int rg, int ns, int nj, int stages);
 int vgpr_estimate(int K, int L, int mb, int rg, int ns, int nj, int softmax);
 

@@ -20,9 +20,10 @@
 //     applied.  The LDS
 //     holds a ring of 2..4 (B tile + D tile) stages, as deep as fits 80 KiB so that two
 //     blocks share a compute unit.
-//   * N_SM of eq. (5) is the number of compute units (256) and N_block counts groups of four
-//     waves (one per SIMD of a compute unit): a block of 8 waves fills a compute unit twice
-//     over, which is what the slowdown factor is about.
+//   * eq. (5) counts parallel work against parallel hardware.  Here the unit is the wave:
+//     N_block := blocks x waves per block, N_SM := 256 compute units x 4 SIMDs x 2 wave slots
+//     (two waves per SIMD is what it takes to overlap the matrix pipe with LDS / VALU work;
+//     measured).  A block of 8 waves therefore counts twice a block of 4.
 #include <math.h>
 #include <string.h>
 
@@ -31,7 +32,9 @@
 
 namespace mcf {
 
-int stages_for(int K, int L, int mb, int rg, int ns, int nj) { return ring_stages(K, L, mb, rg, ns, nj); }
+int stages_for(int K, int L, int mb, int rg, int ns, int nj, int softmax) {
+    return ring_stages(K, L, mb, rg, ns, nj, softmax != 0);
+}
 int lds_bytes_for(int K, int L, int mb, int rg, int ns, int nj, int stages) { return total_lds_bytes(K, L, mb, rg, ns, nj, stages); }
 
 // Registers per lane (eq. (1) restricted to the register-resident tiles, in 32-bit registers):
@@ -66,7 +69,7 @@ static void eval_model(const mcf_problem *p, int softmax, const Variant *v, mcf_
     t->mb = mb; t->rg = rg; t->ns = ns; t->nj = nj;
     t->tm = 32 * mb * rg; t->tn = 32 * ns * nj; t->tk = (int32_t)p->K; t->tl = (int32_t)p->L;
     t->waves = rg * ns;
-    t->stages = stages_for((int)p->K, (int)p->L, mb, rg, ns, nj);
+    t->stages = stages_for((int)p->K, (int)p->L, mb, rg, ns, nj, softmax);
     t->lds_bytes = lds_bytes_for((int)p->K, (int)p->L, mb, rg, ns, nj, t->stages);
     t->vgpr_est = vgpr_estimate((int)p->K, (int)p->L, mb, rg, ns, nj, softmax);
     t->vgpr_used = v->vgprs;
@@ -74,8 +77,8 @@ static void eval_model(const mcf_problem *p, int softmax, const Variant *v, mcf_
     const int64_t es = 2; // bytes per element, fp16 / bf16
     const int64_t m = (p->M + t->tm - 1) / t->tm, n = (p->N + t->tn - 1) / t->tn;
     t->blocks = p->batch * m;
-    // N_block of eq. (5) in units of one wave per SIMD of a compute unit (4 waves)
-    const int64_t units = t->blocks * ((t->waves + 3) / 4);
+    // N_block of eq. (5) counted in waves, against the machine's wave slots (below)
+    const int64_t units = t->blocks * t->waves;
     t->compulsory_bytes = es * p->batch * (p->M * p->K + p->K * p->N + p->N * p->L + p->M * p->L);
     const int64_t la = (int64_t)t->tm * p->K * es * p->batch * m;
     const int64_t lb = (int64_t)p->K * t->tn * es * p->batch * m * n;
@@ -86,7 +89,7 @@ static void eval_model(const mcf_problem *p, int softmax, const Variant *v, mcf_
     const int64_t reread = t->model_bytes > t->compulsory_bytes ? t->model_bytes - t->compulsory_bytes : 0;
     t->t_mem_s = (double)t->compulsory_bytes / kHbmBytesPerSec + (double)reread / kL2BytesPerSec;
     t->t_comp_s = (double)t->flops / kMfmaFlopsPerSec;
-    t->alpha = units > 0 ? (double)(units + kComputeUnits) / (double)units : 1.0;
+    t->alpha = units > 0 ? (double)(units + kWaveSlots) / (double)units : 1.0;
     t->t_est_s = (t->t_mem_s + t->t_comp_s) * t->alpha;
 }
 
