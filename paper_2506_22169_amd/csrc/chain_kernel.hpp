@@ -178,7 +178,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     // Slot -> (row, stored chunk); the global source is the logical chunk = stored ^ swizzle.
     // With clamp (the ragged last tile), rows / columns beyond N are redirected to valid memory
     // (their contribution is masked in registers), so no load ever leaves the tensors.
-    auto bd_offset = [&](int u, int nt0, bool clamp) -> unsigned {
+    auto bd_offset = [&](int u, int nt0, bool clamp) __attribute__((always_inline)) -> unsigned {
         int j = wave + u * W;
         j = j < CT ? j : CT - 1;
         if (j < CB) {
@@ -207,7 +207,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     const int n_iters = (N + TN - 1) / TN;
     const int n_full = N / TN; // tiles [0, n_full) are complete, tile n_full (if any) is ragged
 
-    auto issue_tile = [&](int t, int stage) {
+    auto issue_tile = [&](int t, int stage) __attribute__((always_inline)) {
         const int nt0 = t * TN;
         const void *bbase = uniform((const void *)(BKC ? Bg + (int64_t)nt0 * sb_r : Bg + nt0));
         const void *dbase = uniform((const void *)(Dg + (int64_t)nt0 * sd_r));
@@ -307,21 +307,45 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     }
 
     MCF_TRACE_POINT(4);
-    // LDS -> register operand fetches (sT = base of the ring slot holding the tile).
-    auto load_b = [&](const lds_u8 *sT, int j, int ks) -> v8 {
+    // LDS -> register operand fetches.  The lane-dependent part of every address (row, swizzled
+    // chunk) is computed once, here; per n-tile the ring slot's base is added (one VALU add per
+    // distinct swizzle pattern), and everything else -- slice j, row steps -- is a compile-time
+    // constant in the offset field of the LDS instruction.
+    constexpr int NBV = BKC ? KS : NJ; // B operand: one pattern per k-step (K-contiguous B) or per slice
+    unsigned bvo[NBV], dvo[HB];        // D operand: one pattern per h block
+#pragma unroll
+    for (int i = 0; i < NBV; ++i) bvo[i] = (unsigned)(b_off ^ (BKC ? 32 * i : 64 * i));
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) dvo[hb] = (unsigned)(d_off ^ (64 * hb));
+    unsigned bb[NBV], dd[HB]; // the same plus the base of the ring slot in use
+    auto set_b_slot = [&](unsigned slot_off) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < NBV; ++i) {
+            bb[i] = bvo[i] + slot_off;
+            asm volatile("" : "+v"(bb[i])); // keep the sum in a VGPR: the constant that follows goes to the offset field
+        }
+    };
+    auto set_d_slot = [&](unsigned slot_off) __attribute__((always_inline)) {
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb) {
+            dd[hb] = dvo[hb] + slot_off;
+            asm volatile("" : "+v"(dd[hb]));
+        }
+    };
+    auto load_b = [&](int j, int ks) __attribute__((always_inline)) -> v8 {
         if (MCF_ABLATE & 1) return a[0][ks];
         if (BKC) {
-            return __builtin_bit_cast(v8, *(const lds_u32x4 *)(sT + ((b_off ^ (32 * ks)) + 32 * j * RBB)));
+            return __builtin_bit_cast(v8, *(const lds_u32x4 *)(smem + bb[ks] + 32 * j * RBB));
         } else {
-            const lds_u8 *src = sT + ((b_off ^ (64 * j)) + (16 * ks) * RBB);
+            const lds_u8 *src = smem + bb[j] + (16 * ks) * RBB;
             i16x4 lo = lds_read_tr(src);
             i16x4 hi = lds_read_tr(src + 4 * RBB);
             return __builtin_bit_cast(v8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         }
     };
-    auto load_d = [&](const lds_u8 *sT, int j, int hb, int qp) -> v8 {
+    auto load_d = [&](int j, int hb, int qp) __attribute__((always_inline)) -> v8 {
         if (MCF_ABLATE & 1) return a[0][(2 * hb + qp) % KS];
-        const lds_u8 *src = sT + ((d_off ^ (64 * hb)) + (32 * j + 16 * qp) * RBD);
+        const lds_u8 *src = smem + dd[hb] + (32 * j + 16 * qp) * RBD;
         i16x4 lo = lds_read_tr(src);
         i16x4 hi = lds_read_tr(src + 8 * RBD);
         return __builtin_bit_cast(v8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
@@ -330,10 +354,110 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     // behind the MFMAs already issued; the scheduling barriers keep every LDS read and MFMA
     // in the step it was written in (plain VALU / SALU work may still move across).
     constexpr int PF = 2;
+    constexpr int T1 = NJ * KS;     // MFMA steps of GEMM 1 (each feeds MB MFMAs)
+    constexpr int T2 = NJ * HB * 2; // MFMA steps of GEMM 2
 
-    {
-        constexpr int T1 = NJ * KS;     // MFMA steps of GEMM 1 (each feeds MB MFMAs)
-        constexpr int T2 = NJ * HB * 2; // MFMA steps of GEMM 2
+    f32x16 accC[NJ][MB]; // C^T (then P^T in fp32) of the wave's NJ slices of one n-tile
+    v8 pop[NJ][MB][2];   // the same in 16 bit, as the second MFMA operand of GEMM 2
+    v8 dop[T2];          // D operands of GEMM 2
+
+    // ---- C_C: C^T[n][m] = sum_k B^T[n][k] A^T[k][m], NJ independent 32-column slices -------
+    auto phase_g1 = [&](unsigned slot_off) __attribute__((always_inline)) {
+        set_b_slot(slot_off);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) accC[j][mb][r] = 0.f;
+        v8 bop[T1];
+#pragma unroll
+        for (int t = 0; t < PF && t < T1; ++t) bop[t] = load_b(t / KS, t % KS);
+#pragma unroll
+        for (int t = 0; t < T1; ++t) {
+            const int j = t / KS, ks = t % KS;
+            if (t + PF < T1) bop[t + PF] = load_b((t + PF) / KS, (t + PF) % KS);
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                if (MCF_ABLATE & 2) accC[j][mb][ks] += (float)bop[t][0] * (float)a[mb][ks][1];
+                else accC[j][mb] = M_::run(bop[t], a[mb][ks], accC[j][mb]);
+            }
+            __builtin_amdgcn_sched_barrier(0x406);
+        }
+    };
+    // first D operands of GEMM 2: requested early so that their LDS latency overlaps the
+    // conversion / softmax
+    auto phase_g2_prefetch = [&](unsigned slot_off) __attribute__((always_inline)) {
+        set_d_slot(slot_off);
+#pragma unroll
+        for (int t = 0; t < PF && t < T2; ++t) dop[t] = load_d(t / (2 * HB), (t / 2) % HB, t % 2);
+    };
+    // ---- softmax (online max / sum over n-tiles) and conversion to 16 bit: lane (c,g) holds,
+    //      for row m = c, the columns n = n0 + 32j + 8(r/4) + 4g + r%4
+    auto phase_sm = [&](int n0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            if (n0 + 32 * NJ > N) { // ragged last tile: columns past N contribute nothing
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (n0 + 32 * j + 8 * (r / 4) + 4 * g + (r % 4) >= N) accC[j][mb][r] = SOFTMAX ? -INFINITY : 0.f;
+            }
+            if (SOFTMAX) {
+                float mx = accC[0][mb][0];
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, accC[j][mb][r]);
+                mx = xhalf_max(mx);
+                const float m_new = fmaxf(m_run[mb], mx);
+                const float corr = __builtin_amdgcn_exp2f((m_run[mb] - m_new) * c1);
+                const float mneg = -m_new * c1;
+                float sum = 0.f;
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        accC[j][mb][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(accC[j][mb][r], c1, mneg));
+                        sum += accC[j][mb][r];
+                    }
+                l_run[mb] = l_run[mb] * corr + sum;
+                m_run[mb] = m_new;
+                if (__builtin_amdgcn_ballot_w64(corr != 1.0f)) {
+#pragma unroll
+                    for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) accE[mb][hb][r] *= corr;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int qp = 0; qp < 2; ++qp)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) pop[j][mb][qp][e] = (T)accC[j][mb][8 * qp + e];
+        }
+    };
+    // ---- C_E: E^T[h][m] += sum_n D^T[h][n] P^T[n][m] ---------------------------------------
+    auto phase_g2 = [&]() __attribute__((always_inline)) { // after phase_g2_prefetch of the same tile
+#pragma unroll
+        for (int t = 0; t < T2; ++t) {
+            const int j = t / (2 * HB), hb = (t / 2) % HB, qp = t % 2;
+            if (t + PF < T2) dop[t + PF] = load_d((t + PF) / (2 * HB), ((t + PF) / 2) % HB, (t + PF) % 2);
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                if (MCF_ABLATE & 2) accE[mb][hb][qp] += (float)dop[t][0] * (float)pop[j][mb][qp][1];
+                else accE[mb][hb] = M_::run(dop[t], pop[j][mb][qp], accE[mb][hb]);
+            }
+            __builtin_amdgcn_sched_barrier(0x406);
+        }
+    };
+
+    // Softmax chains in blocks of 8 waves run their two wave groups (waves 0-3 and 4-7, which
+    // share the SIMDs pairwise) a phase apart, see below.
+    constexpr bool SKEW = skewed_groups(RG, NS, SOFTMAX);
+    if constexpr (!SKEW) {
         int stage_c = 0;     // ring slot of the tile being consumed
         int stage_l = S - 1; // ring slot the next issued tile goes to
         for (int it = 0; it < n_iters; ++it) {
@@ -347,100 +471,68 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
                 issue_tile(it + S - 1, stage_l);
                 stage_l = stage_l + 1 == S ? 0 : stage_l + 1;
             }
-
             MCF_TRACE_POINT(9 + 3 * (it & 7));
-            const lds_u8 *sT = smem + stage_c * STAGE;
-            stage_c = stage_c + 1 == S ? 0 : stage_c + 1;
             const int n0 = it * TN + wn * (32 * NJ); // first column of this wave's 32*NJ-wide slice
-
             if (n0 < N) {
-                // ---- C_C: C^T[n][m] = sum_k B^T[n][k] A^T[k][m], NJ independent 32-column slices
-                f32x16 accC[NJ][MB];
-#pragma unroll
-                for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) accC[j][mb][r] = 0.f;
-                v8 bop[T1];
-#pragma unroll
-                for (int t = 0; t < PF && t < T1; ++t) bop[t] = load_b(sT, t / KS, t % KS);
-#pragma unroll
-                for (int t = 0; t < T1; ++t) {
-                    const int j = t / KS, ks = t % KS;
-                    if (t + PF < T1) bop[t + PF] = load_b(sT, (t + PF) / KS, (t + PF) % KS);
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) {
-                        if (MCF_ABLATE & 2) accC[j][mb][ks] += (float)bop[t][0] * (float)a[mb][ks][1];
-                        else accC[j][mb] = M_::run(bop[t], a[mb][ks], accC[j][mb]);
-                    }
-                    __builtin_amdgcn_sched_barrier(0x406);
-                }
-                // first D operands: their LDS latency overlaps the conversion below
-                v8 dop[T2];
-#pragma unroll
-                for (int t = 0; t < PF && t < T2; ++t) dop[t] = load_d(sT, t / (2 * HB), (t / 2) % HB, t % 2);
-
-                // ---- softmax (online max / sum over n-tiles) and conversion to 16 bit: lane (c,g)
-                //      holds, for row m = c, the columns n = n0 + 32j + 8(r/4) + 4g + r%4
-                v8 pop[NJ][MB][2];
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    if (n0 + 32 * NJ > N) { // ragged last tile: columns past N contribute nothing
-#pragma unroll
-                        for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                            for (int r = 0; r < 16; ++r)
-                                if (n0 + 32 * j + 8 * (r / 4) + 4 * g + (r % 4) >= N) accC[j][mb][r] = SOFTMAX ? -INFINITY : 0.f;
-                    }
-                    if (SOFTMAX) {
-                        float mx = accC[0][mb][0];
-#pragma unroll
-                        for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, accC[j][mb][r]);
-                        mx = xhalf_max(mx);
-                        const float m_new = fmaxf(m_run[mb], mx);
-                        const float corr = __builtin_amdgcn_exp2f((m_run[mb] - m_new) * c1);
-                        const float mneg = -m_new * c1;
-                        float sum = 0.f;
-#pragma unroll
-                        for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                            for (int r = 0; r < 16; ++r) {
-                                accC[j][mb][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(accC[j][mb][r], c1, mneg));
-                                sum += accC[j][mb][r];
-                            }
-                        l_run[mb] = l_run[mb] * corr + sum;
-                        m_run[mb] = m_new;
-                        if (__builtin_amdgcn_ballot_w64(corr != 1.0f)) {
-#pragma unroll
-                            for (int hb = 0; hb < HB; ++hb)
-#pragma unroll
-                                for (int r = 0; r < 16; ++r) accE[mb][hb][r] *= corr;
-                        }
-                    }
-#pragma unroll
-                    for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                        for (int qp = 0; qp < 2; ++qp)
-#pragma unroll
-                            for (int e = 0; e < 8; ++e) pop[j][mb][qp][e] = (T)accC[j][mb][8 * qp + e];
-                }
-
-                // ---- C_E: E^T[h][m] += sum_n D^T[h][n] P^T[n][m] ----------------------------
-#pragma unroll
-                for (int t = 0; t < T2; ++t) {
-                    const int j = t / (2 * HB), hb = (t / 2) % HB, qp = t % 2;
-                    if (t + PF < T2) dop[t + PF] = load_d(sT, (t + PF) / (2 * HB), ((t + PF) / 2) % HB, (t + PF) % 2);
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) {
-                        if (MCF_ABLATE & 2) accE[mb][hb][qp] += (float)dop[t][0] * (float)pop[j][mb][qp][1];
-                        else accE[mb][hb] = M_::run(dop[t], pop[j][mb][qp], accE[mb][hb]);
-                    }
-                    __builtin_amdgcn_sched_barrier(0x406);
+                const unsigned st = stage_c * STAGE;
+                phase_g1(st);
+                phase_g2_prefetch(st);
+                phase_sm(n0);
+                phase_g2();
+            }
+            stage_c = stage_c + 1 == S ? 0 : stage_c + 1;
+        }
+    } else {
+        // Per n-tile a wave does G1 (matrix pipe), SM (VALU), G2 (matrix pipe).  Waves w and
+        // w+4 sit on the same SIMD; run in step they would both want the matrix pipe, then both
+        // the VALU.  So the second group runs one phase behind: in iteration i it does SM and G2
+        // of tile i-1 and then G1 of tile i, while the first group does G1, SM, G2 of tile i --
+        // one group's softmax coincides with the other's MFMAs.  One barrier per iteration, as
+        // before; tile i-1 stays in the ring through iteration i, so tile v is requested in
+        // iteration v-S+2 and the ring is at least 3 deep.
+        static_assert(S >= 3, "the skewed loop keeps two tiles live");
+        const int grp = wave >> 2;
+        auto top = [&](int i) __attribute__((always_inline)) {
+            if (i == 0) {
+                if (n_pre == S - 1) wait_vm<(S - 2) * P>();
+                else wait_vm<0>();
+            } else {
+                if (i + S - 3 <= n_iters - 1) wait_vm<(S - 3) * P>();
+                else wait_vm<0>();
+            }
+            __syncthreads(); // tile i is complete for every wave; the slot of tile i-2 is free
+            if (i >= 1 && i + S - 2 < n_iters) issue_tile(i + S - 2, (i + S - 2) % S);
+        };
+        const int ncol0 = wn * (32 * NJ);
+        if (grp == 0) {
+            for (int i = 0; i < n_iters; ++i) {
+                top(i);
+                const int n0 = i * TN + ncol0;
+                if (n0 < N) {
+                    const unsigned st = (i % S) * STAGE;
+                    phase_g1(st);
+                    phase_g2_prefetch(st);
+                    phase_sm(n0);
+                    phase_g2();
                 }
             }
+        } else {
+            auto finish_tile = [&](int t) __attribute__((always_inline)) { // SM and G2 of tile t
+                const int n0 = t * TN + ncol0;
+                if (n0 < N) {
+                    phase_g2_prefetch((t % S) * STAGE);
+                    phase_sm(n0);
+                    phase_g2();
+                }
+            };
+            top(0);
+            if (ncol0 < N) phase_g1(0);
+            for (int i = 1; i < n_iters; ++i) {
+                top(i);
+                finish_tile(i - 1);
+                if (i * TN + ncol0 < N) phase_g1((i % S) * STAGE);
+            }
+            if (n_iters > 0) finish_tile(n_iters - 1);
         }
     }
 

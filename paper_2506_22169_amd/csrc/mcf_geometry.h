@@ -60,8 +60,12 @@ constexpr int pick_stages(int K, int L, int mb, int rg, int ns, int nj, int budg
 // blocks can share the 160 KiB LDS of a compute unit (measured: a deeper ring that costs the
 // second resident block loses more than it gains).
 constexpr int kLdsRingBudget = 80 * 1024;
-constexpr int ring_stages(int K, int L, int mb, int rg, int ns, int nj, bool /*softmax*/) {
-    return pick_stages(K, L, mb, rg, ns, nj, kLdsRingBudget);
+// Softmax chains in blocks of 8 waves run their two wave groups a phase apart, which keeps two
+// n-tiles live: their ring is at least 3 deep.
+constexpr bool skewed_groups(int rg, int ns, bool softmax) { return softmax && rg * ns == 8; }
+constexpr int ring_stages(int K, int L, int mb, int rg, int ns, int nj, bool softmax) {
+    const int s = pick_stages(K, L, mb, rg, ns, nj, kLdsRingBudget);
+    return (skewed_groups(rg, ns, softmax) && s < 3) ? 3 : s;
 }
 
 } // namespace mcf

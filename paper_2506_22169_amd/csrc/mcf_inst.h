@@ -20,7 +20,9 @@
     X(2, 1, 4, 1)          \
     X(4, 2, 4, 1)          \
     X(4, 1, 4, 1)          \
-    X(4, 2, 2, 1)
+    X(4, 2, 2, 1)          \
+    X(1, 8, 1, 1)          \
+    X(1, 8, 1, 2)
 
 #define MCF_ROW(T, DT, K, L, mb, rg, ns, nj, sm, bkc) \
     {DT, K, L, mb, rg, ns, nj, sm, bkc, mcf::launcher_or_null<T, K, L, mb, rg, ns, nj, sm, bkc>()},
