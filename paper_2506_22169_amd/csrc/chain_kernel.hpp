@@ -41,6 +41,11 @@
 #ifndef MCF_TRACE_POINT
 #define MCF_TRACE_POINT(id)
 #endif
+#ifndef MCF_PHASE
+#define MCF_PHASE_DECL
+#define MCF_PHASE(id)
+#define MCF_PHASE_DUMP
+#endif
 // Compile-time ablation mask for experiments (0 in the library): 1 no operand reads from LDS,
 // 2 no MFMA, 4 no combine, 8 no E store, 16 no barrier in the loop, 32 no loads in the loop.
 #ifndef MCF_ABLATE
@@ -153,6 +158,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     const int wave = uniform(tid >> 6);
     const int c = lane & 31, g = lane >> 5;
     const int wr = wave / NS, wn = wave % NS;
+    MCF_PHASE_DECL
 
     // Block index -> (batch, m-tile).  Consecutive hardware block ids go round-robin over the
     // 8 XCDs (each with its own L2); give every XCD a contiguous range of logical blocks so the
@@ -475,10 +481,14 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             const int n0 = it * TN + wn * (32 * NJ); // first column of this wave's 32*NJ-wide slice
             if (n0 < N) {
                 const unsigned st = stage_c * STAGE;
+                MCF_PHASE(0);
                 phase_g1(st);
+                MCF_PHASE(1);
                 phase_g2_prefetch(st);
                 phase_sm(n0);
+                MCF_PHASE(2);
                 phase_g2();
+                MCF_PHASE(3);
             }
             stage_c = stage_c + 1 == S ? 0 : stage_c + 1;
         }
@@ -493,6 +503,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         static_assert(S >= 3, "the skewed loop keeps two tiles live");
         const int grp = wave >> 2;
         auto top = [&](int i) __attribute__((always_inline)) {
+            MCF_PHASE(0);
             if (i == 0) {
                 if (n_pre == S - 1) wait_vm<(S - 2) * P>();
                 else wait_vm<0>();
@@ -500,8 +511,11 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
                 if (i + S - 3 <= n_iters - 1) wait_vm<(S - 3) * P>();
                 else wait_vm<0>();
             }
+            MCF_PHASE(4);
             __syncthreads(); // tile i is complete for every wave; the slot of tile i-2 is free
+            MCF_PHASE(5);
             if (i >= 1 && i + S - 2 < n_iters) issue_tile(i + S - 2, (i + S - 2) % S);
+            MCF_PHASE(6);
         };
         const int ncol0 = wn * (32 * NJ);
         if (grp == 0) {
@@ -510,19 +524,26 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
                 const int n0 = i * TN + ncol0;
                 if (n0 < N) {
                     const unsigned st = (i % S) * STAGE;
+                    MCF_PHASE(0);
                     phase_g1(st);
+                    MCF_PHASE(1);
                     phase_g2_prefetch(st);
                     phase_sm(n0);
+                    MCF_PHASE(2);
                     phase_g2();
+                    MCF_PHASE(3);
                 }
             }
         } else {
             auto finish_tile = [&](int t) __attribute__((always_inline)) { // SM and G2 of tile t
                 const int n0 = t * TN + ncol0;
                 if (n0 < N) {
+                    MCF_PHASE(0);
                     phase_g2_prefetch((t % S) * STAGE);
                     phase_sm(n0);
+                    MCF_PHASE(2);
                     phase_g2();
+                    MCF_PHASE(3);
                 }
             };
             top(0);
@@ -530,12 +551,16 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             for (int i = 1; i < n_iters; ++i) {
                 top(i);
                 finish_tile(i - 1);
-                if (i * TN + ncol0 < N) phase_g1((i % S) * STAGE);
+                if (i * TN + ncol0 < N) {
+                    phase_g1((i % S) * STAGE);
+                    MCF_PHASE(1);
+                }
             }
             if (n_iters > 0) finish_tile(n_iters - 1);
         }
     }
 
+    MCF_PHASE_DUMP
     MCF_TRACE_POINT(5);
     // ---- finish the softmax denominator -----------------------------------------------------
     if (SOFTMAX) {

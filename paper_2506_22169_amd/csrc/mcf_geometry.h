@@ -64,6 +64,9 @@ constexpr int kLdsRingBudget = 80 * 1024;
 // n-tiles live: their ring is at least 3 deep.
 constexpr bool skewed_groups(int rg, int ns, bool softmax) { return softmax && rg * ns == 8; }
 constexpr int ring_stages(int K, int L, int mb, int rg, int ns, int nj, bool softmax) {
+#ifdef MCF_FORCE_STAGES // experiments only
+    return MCF_FORCE_STAGES;
+#endif
     const int s = pick_stages(K, L, mb, rg, ns, nj, kLdsRingBudget);
     return (skewed_groups(rg, ns, softmax) && s < 3) ? 3 : s;
 }

@@ -98,11 +98,14 @@ static bool feasible(const mcf_tiles &t) {
 }
 
 // Strict ordering of candidates: smaller estimate first; among equal estimates (the model
-// does not see how the waves of a block are arranged) more waves per block, then fewer
-// waves across n (less to combine), then fewer rows per wave.
+// does not see how the waves of a block are arranged) more waves per block, then a block
+// whose LDS leaves room for a second one on the compute unit, then fewer waves across n (less
+// to combine), then more column slices per wave, then fewer rows per wave.
 static bool better(const mcf_tiles &a, const mcf_tiles &b) {
     if (a.t_est_s != b.t_est_s) return a.t_est_s < b.t_est_s;
     if (a.waves != b.waves) return a.waves > b.waves;
+    const bool a2 = 2 * a.lds_bytes <= kLdsBytesPerBlock, b2 = 2 * b.lds_bytes <= kLdsBytesPerBlock;
+    if (a2 != b2) return a2;
     if (a.ns != b.ns) return a.ns < b.ns;
     if (a.nj != b.nj) return a.nj > b.nj;
     return a.mb < b.mb;
