@@ -47,7 +47,9 @@ typedef enum {
  *      ([b,N,K] handed over as {N*K, 1, K}: the key matrix of attention, K contiguous).
  *   Every non-unit row stride and every batch stride is a multiple of 8 elements; for
  *   N-contiguous B, N itself is a multiple of 8.  Base pointers are 16-byte aligned.
- * Supported here: K, L in {32, 64, 128}; any batch, M >= 0, N >= 0 (N >= 1 with softmax).
+ * Supported here: (K, L) in {(32,32), (64,64), (128,128), (64,128), (128,64), (64,256),
+ * (256,256)} (the whole K and L extents are kept on chip: T_K = K, T_L = L); any batch,
+ * M >= 0, N >= 0 (N >= 1 with softmax).  Other (K, L) give MCF_EUNSUPPORTED.
  * in_dtype is the type of A, B, D; out_dtype that of E and must equal in_dtype.
  * Both GEMMs accumulate in fp32; C (or P) is rounded once to in_dtype between them.
  */

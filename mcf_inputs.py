@@ -55,6 +55,26 @@ WORKLOADS = {
     "cfg5": Workload("cfg5", 64, 4096, 128, 4096, 128, "bf16", True, "normal", BASE_SEED + 5),
 }
 
+# The shape tables of the paper's evaluation (Sec. VI-B1 Table II: batched GEMM chains G1-G12;
+# Sec. VI-B2 Table III: self-attention modules S1-S9, heads as batch), fp16, same value recipe.
+# Rows as (batch, M, N, K, H).
+_PAPER_GEMM_CHAINS = {
+    "G1": (1, 512, 256, 64, 64), "G2": (1, 512, 256, 64, 128), "G3": (1, 512, 256, 64, 256),
+    "G4": (1, 512, 512, 256, 256), "G5": (1, 512, 512, 512, 256), "G6": (1, 512, 512, 1024, 256),
+    "G7": (1, 512, 512, 128, 128), "G8": (1, 1024, 512, 128, 128), "G9": (1, 2048, 512, 128, 128),
+    "G10": (1, 1024, 1024, 128, 128), "G11": (4, 1024, 1024, 128, 128), "G12": (8, 1024, 1024, 128, 128),
+}
+_PAPER_ATTENTION = {
+    "S1": (8, 512, 512, 64, 64), "S2": (12, 512, 512, 64, 64), "S3": (16, 512, 512, 64, 64),
+    "S4": (12, 256, 256, 64, 64), "S5": (16, 256, 256, 64, 64), "S6": (16, 256, 256, 80, 80),
+    "S7": (1, 512, 256, 64, 64), "S8": (1, 768, 384, 64, 64), "S9": (1, 1024, 512, 64, 64),
+}
+PAPER_SHAPES = {}
+for _i, (_n, (_b, _m, _nn, _k, _h)) in enumerate(_PAPER_GEMM_CHAINS.items()):
+    PAPER_SHAPES[_n] = Workload(_n, _b, _m, _k, _nn, _h, "f16", False, "uniform", BASE_SEED + 100 + _i)
+for _i, (_n, (_b, _m, _nn, _k, _h)) in enumerate(_PAPER_ATTENTION.items()):
+    PAPER_SHAPES[_n] = Workload(_n, _b, _m, _k, _nn, _h, "f16", True, "normal", BASE_SEED + 200 + _i)
+
 
 def _splitmix64(x):
     x = (x + np.uint64(0x9E3779B97F4A7C15)) & _M64

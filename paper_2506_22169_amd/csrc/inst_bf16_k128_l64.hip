@@ -1,0 +1,4 @@
+// Kernel instantiations: bf16 inputs, K = 128, L = 64.
+#include "mcf_inst.h"
+
+MCF_DEFINE_GROUP(__bf16, MCF_BF16, 128, 64, bf16_128_64)

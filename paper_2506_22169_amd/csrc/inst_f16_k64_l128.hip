@@ -1,0 +1,4 @@
+// Kernel instantiations: f16 inputs, K = 64, L = 128.
+#include "mcf_inst.h"
+
+MCF_DEFINE_GROUP(_Float16, MCF_F16, 64, 128, f16_64_128)

@@ -20,7 +20,7 @@ static void packed(int64_t out[3], int64_t rows, int64_t cols) {
 int decode_layout(const mcf_problem *p, Layout *o) {
     if (p->in_dtype != MCF_F16 && p->in_dtype != MCF_BF16) return MCF_EUNSUPPORTED;
     if (p->out_dtype != p->in_dtype) return MCF_EUNSUPPORTED;
-    if (!(p->K == 32 || p->K == 64 || p->K == 128) || p->L != p->K) return MCF_EUNSUPPORTED;
+    if (p->K > 4096 || p->L > 4096 || !group_built(p->in_dtype, (int)p->K, (int)p->L)) return MCF_EUNSUPPORTED;
     if (p->M >= (1ll << 31) - 512 || p->N >= (1ll << 31) - 512 || p->batch >= (1ll << 31)) return MCF_EUNSUPPORTED;
     const int64_t *in[4] = {p->a_stride, p->b_stride, p->d_stride, p->e_stride};
     int64_t *out[4] = {o->sa, o->sb, o->sd, o->se};

@@ -43,6 +43,8 @@ struct Variant {
 
 // Registry of every built kernel variant (defined in mcf_registry.cpp).
 const Variant *variants(int *count);
+// True when kernels for this (dtype, K, L) exist in the library.
+bool group_built(int dtype, int K, int L);
 const Variant *find_variant(int dtype, int K, int L, int softmax, int b_kcontig, int mb, int rg, int ns, int nj);
 
 // Layout decoded from an mcf_problem.

@@ -5,7 +5,9 @@
 
 namespace mcf {
 
-#define MCF_GROUPS(X) X(f16_32_32) X(f16_64_64) X(f16_128_128) X(bf16_32_32) X(bf16_64_64) X(bf16_128_128)
+#define MCF_GROUPS(X)                                                                                      \
+    X(f16_32_32) X(f16_64_64) X(f16_128_128) X(f16_64_128) X(f16_128_64) X(f16_64_256) X(f16_256_256)         \
+    X(bf16_32_32) X(bf16_64_64) X(bf16_128_128) X(bf16_64_128) X(bf16_128_64) X(bf16_64_256) X(bf16_256_256)
 #define MCF_DECL(NAME) const Variant *variants_##NAME(int *count);
 MCF_GROUPS(MCF_DECL)
 
@@ -47,6 +49,12 @@ const Variant *variants(int *count) {
     const auto &t = all();
     *count = (int)t.size();
     return t.data();
+}
+
+bool group_built(int dtype, int K, int L) {
+    for (const Variant &v : all())
+        if (v.dtype == dtype && v.K == K && v.L == L) return true;
+    return false;
 }
 
 const Variant *find_variant(int dtype, int K, int L, int softmax, int b_kcontig, int mb, int rg, int ns, int nj) {

@@ -62,15 +62,18 @@ def test_validation_codes_without_a_launch():
     assert lib.mcf_pick_tiles(ctypes.byref(make_problem(2, 64, 16, 64, 16, "f16")), 0, ctypes.byref(t)) == 2
 
 
-@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+_BUILT_PAPER_SHAPES = [n for n in mi.PAPER_SHAPES if n not in ("G5", "G6", "S6")]
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"] + _BUILT_PAPER_SHAPES)
 def test_picker_terms_match_the_paper_model(name):
     """Every model term of every built variant equals eq. (2)-(5) evaluated by the oracle model
     for the tiling expression mhnk with T_K = K, T_L = L, and the picked variant is the
     feasible one with the smallest estimate."""
-    w = mi.WORKLOADS[name]
+    w = mi.WORKLOADS[name] if name in mi.WORKLOADS else mi.PAPER_SHAPES[name]
     prob = _c_problem(w)
     shapes = mcf.list_variants(prob, w.softmax)
-    assert len(shapes) >= 8
+    assert len(shapes) >= (8 if w.K * w.L <= 128 * 128 else 4)
     dims = {"m": w.M, "n": w.N, "k": w.K, "h": w.L}
     best = None
     for (mb, rg, ns, nj) in shapes:
@@ -106,15 +109,25 @@ def test_picker_terms_match_the_paper_model(name):
     assert pm.padding_ok(w.M, picked.tm) and pm.padding_ok(w.N, picked.tn)
 
 
+def test_paper_shapes_without_kernels_are_refused():
+    """K = 512 / 1024 (G5, G6: they need a k loop inside the block) and K = H = 80 (S6) have
+    no built kernels: the picker says so instead of returning something that cannot run."""
+    lib = mcf.load_library()
+    for name in ("G5", "G6", "S6"):
+        w = mi.PAPER_SHAPES[name]
+        t = Tiles()
+        assert lib.mcf_pick_tiles(ctypes.byref(_c_problem(w)), int(w.softmax), ctypes.byref(t)) == 2, name
+
+
 def test_register_estimate_tracks_the_compiler():
     """The register form of eq. (1): within 30 % below / 60 % above what the compiler allocated,
     and every variant the estimate admits under its register cap compiled without spilling,
     with at most a few exceptions (the analogue of the paper's estimate-vs-lowering check)."""
     total = wrong = 0
     for dtype in ("f16", "bf16"):
-        for KL in (32, 64, 128):
+        for K, L in ((32, 32), (64, 64), (128, 128), (64, 128), (128, 64), (64, 256), (256, 256)):
             for softmax in (False, True):
-                prob = make_problem(4, 1024, KL, 1024, KL, dtype, b_stride=(1024 * KL, 1, KL) if softmax else None)
+                prob = make_problem(4, 1024, K, 1024, L, dtype, b_stride=(1024 * K, 1, K) if softmax else None)
                 for shape in mcf.list_variants(prob, softmax):
                     t = mcf.eval_tiles(prob, *shape, softmax=softmax)
                     cap = 512 // ((t.waves + 3) // 4)
@@ -124,7 +137,7 @@ def test_register_estimate_tracks_the_compiler():
                     if admitted != (t.scratch_bytes == 0):
                         wrong += 1
                     if t.scratch_bytes == 0 and t.vgpr_used < cap:
-                        assert 0.7 * t.vgpr_used <= t.vgpr_est <= 1.6 * t.vgpr_used, (dtype, KL, softmax, shape)
+                        assert 0.7 * t.vgpr_used <= t.vgpr_est <= 1.6 * t.vgpr_used, (dtype, K, L, softmax, shape)
     assert total >= 150 and wrong <= 0.1 * total
 
 
