@@ -36,6 +36,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="cfg2", help="cfg1..cfg5 (default: cfg2, the configuration the metric is quoted on)")
     ap.add_argument("--tiles", default=None, help="mb,rg,ns,nj to override the picker")
+    ap.add_argument("--tune", action="store_true",
+                    help="choose the tiles by the measured search (Alg. 1) before the warm-up instead of by the "
+                         "model alone; candidates are timed as the timed region is (graph replay over the rotating sets)")
     ap.add_argument("--eager", action="store_true", help="time plain calls instead of a HIP graph replay")
     ap.add_argument("--warm", action="store_true", help="reuse one buffer set (cache-resident operands)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -100,6 +103,30 @@ def main():
 
     prob = c_problem(w.batch, w.M, w.K, w.N, w.L, w.dtype,
                      b_stride=(w.N * w.K, 1, w.K) if w.softmax else None)
+    search = None
+    if args.tune and tiles is None:
+        def measure(t):
+            nonlocal tiles
+            tiles = (t.mb, t.rg, t.ns, t.nj)
+            reps = max(2 * n_sets, min(200, args.steps))
+            for i in range(3):
+                step(i)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for i in range(reps):
+                    step(i)
+            g.replay()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e-3 / reps
+        best, rep = mcf.search_tiles(prob, w.softmax, measure, seed=w.seed)
+        tiles = (best.mb, best.rg, best.ns, best.nj)
+        search = {"measured": rep.measured, "generations": rep.generations, "converged": bool(rep.converged),
+                  "best_us": rep.best_t_s * 1e6}
     picked = mcf.pick_tiles(prob, w.softmax) if tiles is None else mcf.eval_tiles(prob, *tiles, softmax=w.softmax)
 
     # ---- warm-up (also sets kernel attributes before any capture) -------------------------
@@ -201,7 +228,8 @@ def main():
                                f"{' softmax' if w.softmax else ''}",
                    "tiles": {"mb": picked.mb, "rg": picked.rg, "ns": picked.ns, "nj": picked.nj, "tm": picked.tm,
                              "tn": picked.tn, "stages": picked.stages},
-                   "buffer_sets": n_sets, "launch": "eager" if args.eager else "hip_graph"},
+                   "buffer_sets": n_sets, "launch": "eager" if args.eager else "hip_graph",
+                   "tile_choice": "search" if search else ("given" if args.tiles else "model"), "search": search},
         "pct_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS, "tflops": tflops,
         "pct_mfma_peak": 100.0 * tflops / MFMA_PEAK_TFLOPS,
         "us_per_launch_events": t_kernel * 1e6,

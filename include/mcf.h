@@ -123,6 +123,69 @@ int mcf_softmax_gemm_chain(const mcf_problem *problem, float scale, const void *
                            const void *B, const void *D, void *E,
                            const mcf_tiles *tiles_or_null, void *hip_stream);
 
+/*
+ * Heuristic search over the built variants (Sec. IV-B, Alg. 1): a population of `population`
+ * candidates drawn at random from the feasible variants (those mcf_pick_tiles would consider),
+ * ranked by the model; the `top_n` distinct candidates with the smallest estimates are measured;
+ * the search stops when the fastest of them is within `epsilon` (relative) of the best time seen
+ * so far, otherwise the next population is drawn from the current one with probability
+ * proportional to 1 / estimate and each drawn member gets the tile choice of one loop (m: the
+ * pair mb, rg; n: the pair ns, nj) replaced by that of a random feasible variant that differs in
+ * that loop only.  A candidate is measured at most once.  Random numbers are SplitMix64 of
+ * (seed + counter).  Zero fields of *params read as the defaults 32, 8, 16 and 0.02.
+ */
+typedef struct mcf_search_params {
+    int32_t population;      /* N of Alg. 1 (default 32)                                   */
+    int32_t top_n;           /* n of Alg. 1 (default 8)                                    */
+    int32_t max_generations; /* bound on the generations, not in Alg. 1 (default 16)       */
+    int32_t reserved;
+    double epsilon;          /* relative convergence threshold (default 0.02)              */
+    uint64_t seed;
+} mcf_search_params;
+
+#define MCF_SEARCH_LOG_MAX 64
+typedef struct mcf_search_entry {
+    int32_t mb, rg, ns, nj;  /* the candidate                                              */
+    int32_t generation;      /* generation (from 0) in which it was measured               */
+    int32_t reserved;
+    double t_est_s;          /* its model estimate, eq. (2)                                */
+    double t_meas_s;         /* what the measurement returned                              */
+} mcf_search_entry;
+
+typedef struct mcf_search_report {
+    int32_t space;           /* feasible variants the search drew from                     */
+    int32_t generations;     /* generations run                                            */
+    int32_t measured;        /* candidates measured (entries of log that are valid)        */
+    int32_t converged;       /* 1: stopped by epsilon, 0: by max_generations               */
+    double best_t_s;         /* measured time of the returned candidate                    */
+    mcf_search_entry log[MCF_SEARCH_LOG_MAX]; /* in measurement order                      */
+} mcf_search_report;
+
+/* Returns the run time in seconds of one launch with these tiles; a negative or non-finite
+ * value aborts the search with MCF_ELAUNCH.  Called on the calling thread. */
+typedef double (*mcf_measure_fn)(const mcf_tiles *candidate, void *user);
+
+/*
+ * Alg. 1 with a caller-supplied measurement.  Host only (the callback may of course launch).
+ * best and report_or_null are host memory.  MCF_EUNSUPPORTED if no variant covers the shape.
+ */
+int mcf_search_tiles(const mcf_problem *problem, int softmax, const mcf_search_params *params_or_null,
+                     mcf_measure_fn measure, void *user, mcf_tiles *best,
+                     mcf_search_report *report_or_null);
+
+/*
+ * Alg. 1 measured on the device: every measured candidate runs 3 + `launches` times on
+ * hip_stream over the caller's buffers (same argument rules as the two chain calls; softmax != 0
+ * selects mcf_softmax_gemm_chain with `scale`), timed with HIP events around the last
+ * `launches` (<= 0 reads as 20).  E is overwritten.  Synchronises hip_stream; creates and
+ * destroys two HIP events, allocates no device memory.  Operands that fit the caches stay
+ * resident between launches, so the times are warm-cache times.
+ */
+int mcf_tune_tiles(const mcf_problem *problem, int softmax, float scale, const void *A,
+                   const void *B, const void *D, void *E, const mcf_search_params *params_or_null,
+                   int launches, void *hip_stream, mcf_tiles *best,
+                   mcf_search_report *report_or_null);
+
 /* Human-readable name of a status code (static storage). */
 const char *mcf_status_string(int status);
 

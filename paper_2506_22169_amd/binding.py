@@ -44,6 +44,34 @@ class Tiles(ctypes.Structure):
         return {n: getattr(self, n) for n, _ in self._fields_}
 
 
+class SearchParams(ctypes.Structure):
+    """struct mcf_search_params"""
+    _fields_ = [("population", ctypes.c_int32), ("top_n", ctypes.c_int32), ("max_generations", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("epsilon", ctypes.c_double), ("seed", ctypes.c_uint64)]
+
+
+class SearchEntry(ctypes.Structure):
+    """struct mcf_search_entry"""
+    _fields_ = [("mb", ctypes.c_int32), ("rg", ctypes.c_int32), ("ns", ctypes.c_int32), ("nj", ctypes.c_int32),
+                ("generation", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("t_est_s", ctypes.c_double), ("t_meas_s", ctypes.c_double)]
+
+
+SEARCH_LOG_MAX = 64
+
+
+class SearchReport(ctypes.Structure):
+    """struct mcf_search_report"""
+    _fields_ = [("space", ctypes.c_int32), ("generations", ctypes.c_int32), ("measured", ctypes.c_int32),
+                ("converged", ctypes.c_int32), ("best_t_s", ctypes.c_double), ("log", SearchEntry * SEARCH_LOG_MAX)]
+
+    def entries(self):
+        return [self.log[i] for i in range(self.measured)]
+
+
+MEASURE_FN = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.POINTER(Tiles), ctypes.c_void_p)
+
+
 def library_path():
     return _LIB_PATH
 
@@ -61,10 +89,13 @@ def load_library():
     lib.mcf_pick_tiles.argtypes = [PP, ctypes.c_int, TP]
     lib.mcf_eval_tiles.argtypes = [PP, ctypes.c_int, TP]
     lib.mcf_list_variants.argtypes = [PP, ctypes.c_int, ctypes.POINTER(ctypes.c_int32), ctypes.c_int]
+    SP, RP = ctypes.POINTER(SearchParams), ctypes.POINTER(SearchReport)
+    lib.mcf_search_tiles.argtypes = [PP, ctypes.c_int, SP, MEASURE_FN, vp, TP, RP]
+    lib.mcf_tune_tiles.argtypes = [PP, ctypes.c_int, ctypes.c_float, vp, vp, vp, vp, SP, ctypes.c_int, vp, TP, RP]
     lib.mcf_gemm_chain.argtypes = [PP, vp, vp, vp, vp, TP, vp]
     lib.mcf_softmax_gemm_chain.argtypes = [PP, ctypes.c_float, vp, vp, vp, vp, TP, vp]
     for f in (lib.mcf_pick_tiles, lib.mcf_eval_tiles, lib.mcf_list_variants, lib.mcf_gemm_chain,
-              lib.mcf_softmax_gemm_chain):
+              lib.mcf_softmax_gemm_chain, lib.mcf_search_tiles, lib.mcf_tune_tiles):
         f.restype = ctypes.c_int
     lib.mcf_status_string.argtypes = [ctypes.c_int]
     lib.mcf_status_string.restype = ctypes.c_char_p
@@ -206,3 +237,50 @@ def list_variants(problem, softmax=False):
     buf = (ctypes.c_int32 * (4 * max(n, 1)))()
     lib.mcf_list_variants(ctypes.byref(problem), int(bool(softmax)), buf, n)
     return [tuple(buf[4 * i:4 * i + 4]) for i in range(n)]
+
+
+def _search_params(population, top_n, epsilon, seed, max_generations):
+    sp = SearchParams()
+    sp.population, sp.top_n, sp.max_generations = int(population), int(top_n), int(max_generations)
+    sp.epsilon, sp.seed = float(epsilon), int(seed)
+    return sp
+
+
+def search_tiles(problem, softmax, measure, population=0, top_n=0, epsilon=0.0, seed=0, max_generations=0):
+    """mcf_search_tiles: Alg. 1 with `measure(Tiles) -> seconds` as the measurement; zero
+    parameters read as the library defaults.  Returns (Tiles, SearchReport)."""
+    failure = []
+
+    def cb(tp, _user):
+        try:
+            return float(measure(tp.contents))
+        except Exception as e:   # an exception cannot cross the C frame: report it as a failed measurement
+            failure.append(e)
+            return -1.0
+
+    sp = _search_params(population, top_n, epsilon, seed, max_generations)
+    best, rep = Tiles(), SearchReport()
+    st = load_library().mcf_search_tiles(ctypes.byref(problem), int(bool(softmax)), ctypes.byref(sp), MEASURE_FN(cb),
+                                         None, ctypes.byref(best), ctypes.byref(rep))
+    if failure:
+        raise failure[0]
+    _check(st)
+    return best, rep
+
+
+def tune_tiles(A, B, D, scale=None, out=None, launches=0, population=0, top_n=0, epsilon=0.0, seed=0,
+               max_generations=0, stream=None):
+    """mcf_tune_tiles: Alg. 1 measured on the device over these tensors (scale=None: plain
+    chain, otherwise the softmax chain).  `out` is overwritten.  Returns (Tiles, SearchReport)."""
+    import torch
+    if out is None:
+        out = torch.empty((A.shape[0], A.shape[1], D.shape[2]), dtype=A.dtype, device=A.device)
+    p = _problem_from_tensors(A, B, D, out)
+    sp = _search_params(population, top_n, epsilon, seed, max_generations)
+    best, rep = Tiles(), SearchReport()
+    _check(load_library().mcf_tune_tiles(
+        ctypes.byref(p), int(scale is not None), ctypes.c_float(0.0 if scale is None else scale),
+        ctypes.c_void_p(A.data_ptr()), ctypes.c_void_p(B.data_ptr()), ctypes.c_void_p(D.data_ptr()),
+        ctypes.c_void_p(out.data_ptr()), ctypes.byref(sp), int(launches), _stream_ptr(stream),
+        ctypes.byref(best), ctypes.byref(rep)))
+    return best, rep

@@ -1,5 +1,6 @@
 // Internal declarations shared by the host files of the library (never installed).
 #pragma once
+#include <vector>
 #include <stdint.h>
 
 #include "../../include/mcf.h"
@@ -58,6 +59,10 @@ int decode_layout(const mcf_problem *p, Layout *out); // MCF_OK or an error stat
 int stages_for(int K, int L, int mb, int rg, int ns, int nj, int softmax);
 int lds_bytes_for(int K, int L, int mb, int rg, int ns, int nj, int stages);
 int vgpr_estimate(int K, int L, int mb, int rg, int ns, int nj, int softmax);
+
+// Feasible candidates for a problem, with their model terms, in registry order (the set
+// mcf_pick_tiles chooses from).  MCF_OK, or the status mcf_pick_tiles would return.
+int feasible_candidates(const mcf_problem *p, int softmax, std::vector<mcf_tiles> *out);
 
 void set_last_error(const char *msg);
 

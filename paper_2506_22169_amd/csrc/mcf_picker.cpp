@@ -28,6 +28,8 @@
 #include <string.h>
 
 #include "mcf_geometry.h"
+#include <vector>
+
 #include "mcf_internal.h"
 
 namespace mcf {
@@ -150,18 +152,17 @@ extern "C" int mcf_eval_tiles(const mcf_problem *p, int softmax, mcf_tiles *t) {
     return feasible(*t) ? MCF_OK : MCF_EINVAL;
 }
 
-extern "C" int mcf_pick_tiles(const mcf_problem *p, int softmax, mcf_tiles *out) {
+// The candidates the picker and the search choose from, in registry order: feasible variants
+// that satisfy Rule 3; if Rule 3 leaves nothing (e.g. M smaller than every tile) it is dropped
+// so that a feasible variant is always found when one covers the shape.
+int mcf::feasible_candidates(const mcf_problem *p, int softmax, std::vector<mcf_tiles> *out) {
     Layout lay;
-    if (!out) return MCF_EINVAL;
     int st = check_problem(p, &lay);
     if (st != MCF_OK) return st;
     int n = 0;
     const Variant *v = variants(&n);
-    // Two passes: with Rule 3, and without it if Rule 3 leaves nothing (e.g. M smaller than
-    // every tile), so that a feasible variant is always found when one covers the shape.
     for (int pass = 0; pass < 2; ++pass) {
-        bool have = false;
-        mcf_tiles best;
+        out->clear();
         for (int i = 0; i < n; ++i) {
             if (v[i].dtype != p->in_dtype || v[i].K != p->K || v[i].L != p->L || v[i].softmax != (softmax != 0) ||
                 v[i].b_kcontig != lay.b_kcontig)
@@ -170,9 +171,21 @@ extern "C" int mcf_pick_tiles(const mcf_problem *p, int softmax, mcf_tiles *out)
             eval_model(p, softmax != 0, &v[i], &t);
             if (!feasible(t)) continue;
             if (pass == 0 && p->M > 0 && p->N > 0 && !(padding_ok(p->M, t.tm) && padding_ok(p->N, t.tn))) continue;
-            if (!have || better(t, best)) { best = t; have = true; }
+            out->push_back(t);
         }
-        if (have) { *out = best; return MCF_OK; }
+        if (!out->empty()) return MCF_OK;
     }
     return MCF_EUNSUPPORTED;
+}
+
+extern "C" int mcf_pick_tiles(const mcf_problem *p, int softmax, mcf_tiles *out) {
+    if (!out) return MCF_EINVAL;
+    std::vector<mcf_tiles> cands;
+    int st = feasible_candidates(p, softmax, &cands);
+    if (st != MCF_OK) return st;
+    const mcf_tiles *best = &cands[0];
+    for (const mcf_tiles &t : cands)
+        if (better(t, *best)) best = &t;
+    *out = *best;
+    return MCF_OK;
 }
