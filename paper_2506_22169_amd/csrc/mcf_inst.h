@@ -23,7 +23,9 @@
     X(4, 1, 4, 1)          \
     X(4, 2, 2, 1)          \
     X(1, 8, 1, 1)          \
-    X(1, 8, 1, 2)
+    X(1, 8, 1, 2)          \
+    X(2, 4, 2, 1)          \
+    X(2, 4, 2, 2)
 
 namespace mcf {
 
