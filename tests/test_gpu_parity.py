@@ -167,3 +167,67 @@ def test_error_codes_from_the_abi():
     with pytest.raises(mcf.McfError) as e:          # no such wave arrangement
         mcf.gemm_chain(A, B, D, tiles=(3, 1, 1, 1))
     assert e.value.status == 1
+
+
+def test_random_shapes_strides_and_tiles():
+    """Seeded sweep: random (K, L) group, dtype, chain kind, B layout, ragged or tiny M and N,
+    non-packed row and batch strides on every operand and on the output, and a random built
+    wave arrangement, each compared with the oracle element by element; the padding around a
+    strided output must come back untouched."""
+    rng = np.random.default_rng(20250622)
+    groups = [(32, 32), (64, 64), (128, 128), (64, 128), (128, 64), (64, 256), (256, 256)]
+    sizes = [1, 2, 7, 31, 32, 33, 64, 100, 129, 255, 300, 517]
+    worst = 0.0
+    for case in range(48):
+        K, L = groups[rng.integers(len(groups))]
+        dtype = ("f16", "bf16")[rng.integers(2)]
+        softmax = bool(rng.integers(2))
+        nk = bool(rng.integers(2))                                  # B stored [b,N,K] (K contiguous)
+        b = int(rng.integers(1, 4))
+        M = int(sizes[rng.integers(len(sizes))])
+        N = int(sizes[rng.integers(len(sizes))])
+        if not nk:
+            N = max(8, (N + 7) // 8 * 8)                            # N-contiguous B: N a multiple of 8
+        pad = [int(8 * rng.integers(0, 3)) for _ in range(4)]       # extra row pitch of A, B, D, E
+        gap = [int(rng.integers(0, 3)) for _ in range(4)]           # extra rows between batches
+        w = mi.make_problem(b, M, K, N, L, dtype, softmax, "normal" if softmax else "uniform", seed=9000 + case)
+        x = mi.make_inputs(w)
+        tdt = torch.float16 if dtype == "f16" else torch.bfloat16
+
+        def strided(t, rows, cols, pad_c, gap_r, fill=0.0):
+            big = torch.full((b, rows + gap_r, cols + pad_c), fill, dtype=tdt, device="cuda")
+            big[:, :rows, :cols] = t
+            return big, big[:, :rows, :cols]
+
+        A0 = to_device(x["a_bits"], dtype)
+        D0 = to_device(x["d_bits"], dtype)
+        Bs = to_device(x["b_bits"], dtype)                           # [b,N,K] if b_layout == "nk" else [b,K,N]
+        Bkn = Bs.transpose(1, 2) if x["b_layout"] == "nk" else Bs    # logical [b,K,N]
+        _, A = strided(A0, M, K, pad[0], gap[0])
+        if nk:
+            _, Bnk = strided(Bkn.transpose(1, 2), N, K, pad[1], gap[1])
+            B = Bnk.transpose(1, 2)
+        else:
+            _, B = strided(Bkn, K, N, pad[1], gap[1])
+        _, D = strided(D0, N, L, pad[2], gap[2])
+        Ebig, E = strided(torch.zeros((b, M, L), dtype=tdt, device="cuda"), M, L, pad[3], gap[3], fill=5.0)
+        prob = mcf.binding._problem_from_tensors(A, B, D, E)
+        shapes = [s for s in mcf.list_variants(prob, softmax)]
+        tiles = shapes[rng.integers(len(shapes))] if case % 4 else None   # every fourth case: the picker
+        print(f"case {case}: b={b} M={M} K={K} N={N} L={L} {dtype} softmax={softmax} nk={nk} pad={pad} gap={gap} "
+              f"tiles={tiles}", flush=True)
+        if softmax:
+            mcf.softmax_gemm_chain(A, B, D, w.scale, out=E, tiles=tiles)
+        else:
+            mcf.gemm_chain(A, B, D, out=E, tiles=tiles)
+        torch.cuda.synchronize()
+        ref = oracle.chain(x["A"], x["B"], x["D"], softmax=softmax, scale=w.scale)
+        got = to_host64(E, dtype)
+        scale = np.max(np.abs(ref))
+        err = np.max(np.abs(got - ref))
+        assert err <= TOL * scale, f"case {case}: {err} > {TOL} * {scale}"
+        worst = max(worst, err / scale if scale else 0.0)
+        outside = Ebig.clone()
+        outside[:, :M, :L] = 5.0
+        assert bool((outside == 5.0).all()), f"case {case}: wrote outside the output view"
+    print(f"worst max|err|/max|oracle| = {worst:.3e}", flush=True)
