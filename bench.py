@@ -34,7 +34,8 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--workload", default="cfg2", help="cfg1..cfg5 (default: cfg2, the configuration the metric is quoted on)")
+    ap.add_argument("--workload", default="cfg2", help="cfg1..cfg5 (default: cfg2, the configuration the metric is quoted on), or a row of the "
+                                                      "paper's shape tables: G1..G12, S1..S5, S7..S9")
     ap.add_argument("--tiles", default=None, help="mb,rg,ns,nj to override the picker")
     ap.add_argument("--tune", action="store_true",
                     help="choose the tiles by the measured search (Alg. 1) before the warm-up instead of by the "
@@ -69,7 +70,7 @@ def main():
         return 2
     mcf.load_library()  # fail loudly if the HIP library is not built
 
-    w = mi.WORKLOADS[args.workload]
+    w = mi.WORKLOADS[args.workload] if args.workload in mi.WORKLOADS else mi.PAPER_SHAPES[args.workload]
     tdt = torch.float16 if w.dtype == "f16" else torch.bfloat16
     tiles = tuple(int(v) for v in args.tiles.split(",")) if args.tiles else None
 

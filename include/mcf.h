@@ -48,8 +48,10 @@ typedef enum {
  *   Every non-unit row stride and every batch stride is a multiple of 8 elements; for
  *   N-contiguous B, N itself is a multiple of 8.  Base pointers are 16-byte aligned.
  * Supported here: (K, L) in {(32,32), (64,64), (128,128), (64,128), (128,64), (64,256),
- * (256,256)} (the whole K and L extents are kept on chip: T_K = K, T_L = L); any batch,
- * M >= 0, N >= 0 (N >= 1 with softmax).  Other (K, L) give MCF_EUNSUPPORTED.
+ * (256,256)} with the whole K extent on chip (T_K = K), and every other K >= 256 that is a
+ * multiple of 128 with L in {64, 128, 256} through kernels with a k loop inside the block
+ * (T_K = 128); T_L = L always.  Any batch, M >= 0, N >= 0 (N >= 1 with softmax).  Other
+ * (K, L) give MCF_EUNSUPPORTED.
  * in_dtype is the type of A, B, D; out_dtype that of E and must equal in_dtype.
  * Both GEMMs accumulate in fp32; C (or P) is rounded once to in_dtype between them.
  */
@@ -69,7 +71,7 @@ typedef struct mcf_problem {
  * 32-column slices), waves = rg * ns.
  */
 typedef struct mcf_tiles {
-    int32_t tm, tn, tk, tl;   /* tile sizes T_M, T_N, T_K (= K), T_L (= L)                       */
+    int32_t tm, tn, tk, tl;   /* tile sizes T_M, T_N, T_K (= K, or 128 with a k loop), T_L (= L) */
     int32_t mb, rg, ns, nj;   /* 32-row blocks per wave, wave row-groups, waves across n,        */
                               /* 32-column slices per wave and n-iteration (0 reads as 1)        */
     int32_t waves;            /* rg * ns, 64 lanes each                                          */

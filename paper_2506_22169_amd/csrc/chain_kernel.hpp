@@ -119,7 +119,10 @@ template <int N> static __device__ __forceinline__ void wait_vm() {
     static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
-template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool BKC>
+// KSPLIT: KD is the chunk T_K of a k loop inside the block (K = k_chunks * KD); the A chunk of
+// every k step travels through the LDS ring with the B chunk instead of the whole A tile living
+// in registers.
+template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool BKC, bool KSPLIT = false>
 __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     using M_ = Mfma<T>;
     using v8 = typename M_::v8;
@@ -128,17 +131,23 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     constexpr int TN = 32 * NS * NJ;     // columns per n-iteration
     constexpr int KS = KD / 16;          // MFMA k-steps of GEMM 1
     constexpr int HB = LD / 32;          // 32-wide h blocks of GEMM 2
-    constexpr int S = ring_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX); // depth of the LDS ring
+    constexpr int S = ring_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX, KSPLIT); // depth of the LDS ring
     constexpr int RBA = 2 * KD;                  // row bytes of the A tile (rows m)
     constexpr int RBB = BKC ? 2 * KD : 2 * TN;   // row bytes of the B tile (rows n / rows k)
     constexpr int RBD = 2 * LD;                  // row bytes of the D tile (rows n)
     constexpr int RBE = 2 * LD;                  // row bytes of the E staging tile (rows m)
     constexpr int B_BYTES = b_tile_bytes(KD, TN);
-    constexpr int STAGE = stage_bytes(KD, LD, TN);
-    constexpr int A_LDS = (S - 1) * STAGE;       // the A tile borrows the last ring slot
+    constexpr int A_BYTES = a_tile_bytes(KD, MB, RG);
+    // Without a k loop a ring slot holds [B tile | D tile] and the A tile borrows the last slot
+    // once; with one, a slot holds either [A chunk | B chunk] or [D tile].
+    constexpr int STAGE = KSPLIT ? ksplit_slot_bytes(KD, LD, MB, RG, TN) : stage_bytes(KD, LD, TN);
+    constexpr int A_LDS = KSPLIT ? 0 : (S - 1) * STAGE; // offset of the A tile (chunk: within its slot)
+    constexpr int B_LDS = KSPLIT ? A_BYTES : 0;         // offset of the B tile within its slot
+    constexpr int D_LDS = KSPLIT ? 0 : B_BYTES;         // offset of the D tile within its slot
     // 1 KiB wave-loads per tile and per wave
-    constexpr int CA = a_tile_bytes(KD, MB, RG) / 1024;
-    constexpr int CB = B_BYTES / 1024, CT = STAGE / 1024;
+    constexpr int CA = A_BYTES / 1024;
+    constexpr int CB = B_BYTES / 1024, CD = d_tile_bytes(LD, TN) / 1024;
+    constexpr int CT = KSPLIT ? (CA + CB > CD ? CA + CB : CD) : CB + CD; // wave-loads of the largest item
     constexpr int PA = (CA + W - 1) / W;
     constexpr int P = (CT + W - 1) / W;
     static_assert((S - 1) * P <= 63, "too many loads in flight for the 6-bit vmcnt counter");
@@ -207,8 +216,10 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         }
     };
     unsigned voff[P];
+    if constexpr (!KSPLIT) {
 #pragma unroll
-    for (int u = 0; u < P; ++u) voff[u] = bd_offset(u, 0, false);
+        for (int u = 0; u < P; ++u) voff[u] = bd_offset(u, 0, false);
+    }
 
     const int n_iters = (N + TN - 1) / TN;
     const int n_full = N / TN; // tiles [0, n_full) are complete, tile n_full (if any) is ragged
@@ -235,8 +246,76 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         }
     };
 
+    // ---- kernels with a k loop: the items that travel through the ring ----------------------
+    // Item r of n-tile t: r < KC is the A chunk + B chunk of k step r ([A | B] in the slot),
+    // r == KC the D tile.  Every wave issues P wave-loads per item (the last one repeated where
+    // an item has fewer), so that the counted waits are the same for both kinds.
+    const int KC = KSPLIT ? p.k_chunks : 1;
+    constexpr int CAB = CA + CB;
+    auto ks_offset = [&](bool d_item, int u, int nt0, bool clamp) __attribute__((always_inline)) -> unsigned {
+        int j = wave + u * W;
+        if (d_item) {
+            j = j < CD ? j : CD - 1;
+            const int slot = 64 * j + lane;
+            int row = slot / (RBD / 16), ch = slot % (RBD / 16);
+            ch ^= swz_tr(RBD, row);
+            if (clamp && nt0 + row >= N) row = N - 1 - nt0;
+            return (unsigned)(row * sd_r * 2 + ch * 16);
+        }
+        j = j < CAB ? j : CAB - 1;
+        if (j < CA) {
+            const int slot = 64 * j + lane;
+            int row = slot / (RBA / 16), ch = slot % (RBA / 16);
+            ch ^= swz_b128(RBA, row);
+            if (mrow0 + row >= M) row = M - 1 - mrow0; // rows past M: any valid row, never stored
+            return (unsigned)(row * sa_r * 2 + ch * 16);
+        }
+        const int slot = 64 * (j - CA) + lane;
+        int row = slot / (RBB / 16), ch = slot % (RBB / 16);
+        if (BKC) {
+            ch ^= swz_b128(RBB, row);
+            if (clamp && nt0 + row >= N) row = N - 1 - nt0;
+        } else {
+            ch ^= swz_tr(RBB, row);
+            if (clamp && nt0 + 8 * ch >= N) ch = 0;
+        }
+        return (unsigned)(row * sb_r * 2 + ch * 16);
+    };
+    unsigned voff_d[KSPLIT ? P : 1];
+    if constexpr (KSPLIT) {
+#pragma unroll
+        for (int u = 0; u < P; ++u) {
+            voff[u] = ks_offset(false, u, 0, false);
+            voff_d[u] = ks_offset(true, u, 0, false);
+        }
+    }
+    auto issue_item = [&](int t, int r, int stage) __attribute__((always_inline)) {
+        const int nt0 = t * TN;
+        const unsigned dst0 = uniform(lds0 + stage * STAGE + wave * 1024);
+        const bool ragged = t >= n_full;
+        if (r < KC) {
+            const int64_t k0 = (int64_t)r * KD;
+            const void *abase = uniform((const void *)(Ag + k0));
+            const void *bbase = uniform((const void *)(BKC ? Bg + (int64_t)nt0 * sb_r + k0 : Bg + k0 * sb_r + nt0));
+#pragma unroll
+            for (int u = 0; u < P; ++u) {
+                const int j = wave + u * W; // wave-uniform
+                const int jj = j < CAB ? j : CAB - 1;
+                dma16(dst0 + (jj - wave) * 1024, ragged ? ks_offset(false, u, nt0, true) : voff[u], jj < CA ? abase : bbase);
+            }
+        } else {
+            const void *dbase = uniform((const void *)(Dg + (int64_t)nt0 * sd_r));
+#pragma unroll
+            for (int u = 0; u < P; ++u) {
+                const int j = wave + u * W;
+                const int jj = j < CD ? j : CD - 1;
+                dma16(dst0 + (jj - wave) * 1024, ragged ? ks_offset(true, u, nt0, true) : voff_d[u], dbase);
+            }
+        }
+    };
+
     // ---- prologue: A tile (into the last ring slot) and the first S-1 n-tiles ---------------
-    {
+    if constexpr (!KSPLIT) {
         const void *abase = uniform((const void *)Ag);
         const unsigned dst0 = uniform(lds0 + A_LDS + wave * 1024);
 #pragma unroll
@@ -250,30 +329,40 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             dma16(dst0 + (jj - wave) * 1024, (unsigned)(row * sa_r * 2 + ch * 16), abase);
         }
     }
-    const int n_pre = n_iters < S - 1 ? n_iters : S - 1;
-    for (int t = 0; t < n_pre; ++t) issue_tile(t, t);
+    const int n_items = KSPLIT ? n_iters * (KC + 1) : n_iters; // ring items of the whole block
+    const int n_pre = n_items < S - 1 ? n_items : S - 1;
+    if constexpr (KSPLIT) {
+        for (int q = 0; q < n_pre; ++q) issue_item(q / (KC + 1), q % (KC + 1), q);
+    } else {
+        for (int t = 0; t < n_pre; ++t) issue_tile(t, t);
+    }
     MCF_TRACE_POINT(1);
-    // the A loads are older than the n_pre tile groups
-    if (n_pre == S - 1) wait_vm<(S - 1) * P>();
-    else wait_vm<0>();
-    MCF_TRACE_POINT(2);
-    __syncthreads();
-    MCF_TRACE_POINT(3);
 
-    // ---- L_A: A tile -> registers, as the second MFMA operand A^T[k][m] ------------------
+    // ---- L_A: A tile (or chunk) in LDS -> registers, as the second MFMA operand A^T[k][m] ---
     v8 a[MB][KS];
+    auto load_a = [&](unsigned base) __attribute__((always_inline)) {
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-        const int row = wr * (32 * MB) + 32 * mb + c;
-        const lds_u8 *src = smem + A_LDS + row * RBA;
-        const int sw = swz_b128(RBA, row);
+        for (int mb = 0; mb < MB; ++mb) {
+            const int row = wr * (32 * MB) + 32 * mb + c;
+            const lds_u8 *src = smem + base + row * RBA;
+            const int sw = swz_b128(RBA, row);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            u32x4 raw = *(const lds_u32x4 *)(src + 16 * ((2 * ks + g) ^ sw));
-            if (a_mode == 1) raw ^= 0x80008000u; // flip the sign of all eight 16-bit floats
-            if (a_mode == 2) raw = u32x4{0u, 0u, 0u, 0u};
-            a[mb][ks] = __builtin_bit_cast(v8, raw);
+            for (int ks = 0; ks < KS; ++ks) {
+                u32x4 raw = *(const lds_u32x4 *)(src + 16 * ((2 * ks + g) ^ sw));
+                if (a_mode == 1) raw ^= 0x80008000u; // flip the sign of all eight 16-bit floats
+                if (a_mode == 2) raw = u32x4{0u, 0u, 0u, 0u};
+                a[mb][ks] = __builtin_bit_cast(v8, raw);
+            }
         }
+    };
+    if constexpr (!KSPLIT) {
+        // the A loads are older than the n_pre tile groups
+        if (n_pre == S - 1) wait_vm<(S - 1) * P>();
+        else wait_vm<0>();
+        MCF_TRACE_POINT(2);
+        __syncthreads();
+        MCF_TRACE_POINT(3);
+        load_a(A_LDS);
     }
 
     // ---- loop-invariant LDS read offsets of this lane --------------------------------------
@@ -282,12 +371,12 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     if (BKC) {
         // first MFMA operand B^T[n][k]: row n = (wn*NJ + j)*32 + c, logical chunk 2ks + g
         const int row = wn * NJ * 32 + c;
-        b_off = row * RBB + 16 * (g ^ swz_b128(RBB, row)); // per k-step: ^ (32 ks); per j: + 32 j rows
+        b_off = B_LDS + row * RBB + 16 * (g ^ swz_b128(RBB, row)); // per k-step: ^ (32 ks); per j: + 32 j rows
     } else {
         // rows k = 16ks + 8g + i/4 (+4), columns n = (wn*NJ + j)*32 + 16u + 4(i%4) .. +3
         const int row = 8 * g + (i16 >> 2);
         const int ch = (4 * wn * NJ + 2 * u16 + ((i16 >> 1) & 1)) ^ swz_tr(RBB, row);
-        b_off = row * RBB + 16 * ch + 8 * (i16 & 1); // per j: ^ (64 j) bytes (NJ is a power of two)
+        b_off = B_LDS + row * RBB + 16 * ch + 8 * (i16 & 1); // per j: ^ (64 j) bytes (NJ is a power of two)
     }
     // D operand of GEMM 2 (first MFMA operand D^T[h][n]).  MFMA row i of the h block is mapped
     // to h = 16*((i>>2)&1) + 4*(i>>3) + (i&3) so that the accumulator of lane (c,g) ends up
@@ -297,7 +386,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         const int x4 = i16 & 3;
         const int row = wn * NJ * 32 + 4 * g + (i16 >> 2); // per j: + 32 j rows
         const int ch = (u16 + 2 * (x4 & 1)) ^ swz_tr(RBD, row); // h block 0; per hb: ^ (64 hb) bytes
-        d_off = B_BYTES + row * RBD + 16 * ch + 8 * (x4 >> 1);
+        d_off = D_LDS + row * RBD + 16 * ch + 8 * (x4 >> 1);
     }
 
     f32x16 accE[MB][HB];
@@ -368,14 +457,16 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     v8 dop[T2];          // D operands of GEMM 2
 
     // ---- C_C: C^T[n][m] = sum_k B^T[n][k] A^T[k][m], NJ independent 32-column slices -------
-    auto phase_g1 = [&](unsigned slot_off) __attribute__((always_inline)) {
+    auto phase_g1 = [&](unsigned slot_off, bool first = true) __attribute__((always_inline)) {
         set_b_slot(slot_off);
+        if (first) { // with a k loop: the first chunk of an n-tile
 #pragma unroll
-        for (int j = 0; j < NJ; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
+                for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) accC[j][mb][r] = 0.f;
+                    for (int r = 0; r < 16; ++r) accC[j][mb][r] = 0.f;
+        }
         v8 bop[T1];
 #pragma unroll
         for (int t = 0; t < PF && t < T1; ++t) bop[t] = load_b(t / KS, t % KS);
@@ -462,8 +553,40 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
 
     // Softmax chains in blocks of 8 waves run their two wave groups (waves 0-3 and 4-7, which
     // share the SIMDs pairwise) a phase apart, see below.
-    constexpr bool SKEW = skewed_groups(RG, NS, SOFTMAX);
-    if constexpr (!SKEW) {
+    constexpr bool SKEW = skewed_groups(RG, NS, SOFTMAX, KSPLIT);
+    if constexpr (KSPLIT) {
+        // One ring item per iteration: the k steps of an n-tile accumulate C^T, its D item turns
+        // C^T into P^T and feeds GEMM 2.  Same protocol as below: one barrier per item, loads
+        // S-1 items ahead.
+        const int NI = KC + 1;
+        int stage_c = 0, stage_l = S - 1;
+        int lt = n_pre / NI, lr = n_pre % NI; // next item to request
+        int ct = 0, cr = 0;                   // item being consumed
+        for (int q = 0; q < n_items; ++q) {
+            if (n_items - q >= S - 1) wait_vm<(S - 2) * P>();
+            else wait_vm<0>();
+            __syncthreads(); // item q is complete for every wave; the slot of item q-1 is free
+            if (q + S - 1 < n_items) {
+                issue_item(lt, lr, stage_l);
+                if (++lr == NI) { lr = 0; ++lt; }
+                stage_l = stage_l + 1 == S ? 0 : stage_l + 1;
+            }
+            const int n0 = ct * TN + wn * (32 * NJ);
+            if (n0 < N) {
+                const unsigned st = stage_c * STAGE;
+                if (cr < KC) {
+                    load_a(st + A_LDS);
+                    phase_g1(st, cr == 0);
+                } else {
+                    phase_g2_prefetch(st);
+                    phase_sm(n0);
+                    phase_g2();
+                }
+            }
+            if (++cr == NI) { cr = 0; ++ct; }
+            stage_c = stage_c + 1 == S ? 0 : stage_c + 1;
+        }
+    } else if constexpr (!SKEW) {
         int stage_c = 0;     // ring slot of the tile being consumed
         int stage_l = S - 1; // ring slot the next issued tile goes to
         for (int it = 0; it < n_iters; ++it) {
@@ -696,10 +819,10 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
 }
 
 // Host-side launcher of one instantiation.
-template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool BKC>
+template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool BKC, bool KSPLIT = false>
 int launch_chain(const KParams &p, void *stream) {
-    constexpr int lds = total_lds_bytes(KD, LD, MB, RG, NS, NJ, ring_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX));
-    auto kern = chain_kernel<T, KD, LD, MB, RG, NS, NJ, SOFTMAX, BKC>;
+    constexpr int lds = total_lds_bytes(KD, LD, MB, RG, NS, NJ, ring_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX, KSPLIT), KSPLIT);
+    auto kern = chain_kernel<T, KD, LD, MB, RG, NS, NJ, SOFTMAX, BKC, KSPLIT>;
     static bool attr_done = false; // benign race: setting the attribute twice is harmless
     if (lds > 64 * 1024 && !attr_done) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -712,10 +835,10 @@ int launch_chain(const KParams &p, void *stream) {
 
 // Launcher of an instantiation, or nullptr when the wave arrangement cannot exist for this
 // (K, L): more LDS than a compute unit has.  Such kernels are not compiled at all.
-template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool BKC>
+template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool BKC, bool KSPLIT = false>
 constexpr LaunchFn launcher_or_null() {
-    if constexpr (total_lds_bytes(KD, LD, MB, RG, NS, NJ, ring_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX)) <= kLdsBytesPerBlock)
-        return &launch_chain<T, KD, LD, MB, RG, NS, NJ, SOFTMAX, BKC>;
+    if constexpr (total_lds_bytes(KD, LD, MB, RG, NS, NJ, ring_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX, KSPLIT), KSPLIT) <= kLdsBytesPerBlock)
+        return &launch_chain<T, KD, LD, MB, RG, NS, NJ, SOFTMAX, BKC, KSPLIT>;
     else
         return nullptr;
 }

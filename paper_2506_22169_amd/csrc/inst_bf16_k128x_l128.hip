@@ -1,0 +1,4 @@
+// Kernel instantiations with a k loop: bf16 inputs, K a multiple of T_K = 128, L = 128.
+#include "mcf_inst.h"
+
+MCF_DEFINE_KSPLIT_GROUP(__bf16, MCF_BF16, 128, 128, bf16_k128x_128)

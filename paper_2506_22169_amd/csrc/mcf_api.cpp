@@ -20,7 +20,10 @@ static void packed(int64_t out[3], int64_t rows, int64_t cols) {
 int decode_layout(const mcf_problem *p, Layout *o) {
     if (p->in_dtype != MCF_F16 && p->in_dtype != MCF_BF16) return MCF_EUNSUPPORTED;
     if (p->out_dtype != p->in_dtype) return MCF_EUNSUPPORTED;
-    if (p->K > 4096 || p->L > 4096 || !group_built(p->in_dtype, (int)p->K, (int)p->L)) return MCF_EUNSUPPORTED;
+    {
+        int tk = 0, ksplit = 0;
+        if (p->K > 65536 || p->L > 4096 || !resolve_group(p->in_dtype, p->K, p->L, &tk, &ksplit)) return MCF_EUNSUPPORTED;
+    }
     if (p->M >= (1ll << 31) - 512 || p->N >= (1ll << 31) - 512 || p->batch >= (1ll << 31)) return MCF_EUNSUPPORTED;
     const int64_t *in[4] = {p->a_stride, p->b_stride, p->d_stride, p->e_stride};
     int64_t *out[4] = {o->sa, o->sb, o->sd, o->se};
@@ -93,10 +96,9 @@ static int run(const mcf_problem *p, int softmax, float scale, const void *A, co
         st = mcf_pick_tiles(p, softmax, &chosen);
         if (st != MCF_OK) return st;
     }
-    const Variant *v = find_variant(p->in_dtype, (int)p->K, (int)p->L, softmax, lay.b_kcontig, chosen.mb, chosen.rg, chosen.ns, chosen.nj > 0 ? chosen.nj : 1);
+    const Variant *v = find_variant(p->in_dtype, p->K, p->L, softmax, lay.b_kcontig, chosen.mb, chosen.rg, chosen.ns, chosen.nj > 0 ? chosen.nj : 1);
     if (!v) return tiles ? MCF_EINVAL : MCF_EUNSUPPORTED;
-    if (lds_bytes_for((int)p->K, (int)p->L, v->mb, v->rg, v->ns, v->nj, stages_for((int)p->K, (int)p->L, v->mb, v->rg, v->ns, v->nj, softmax)) >
-        kLdsBytesPerBlock)
+    if (lds_bytes_for(v) > kLdsBytesPerBlock)
         return MCF_EINVAL; // more LDS than a compute unit has
 
     const int64_t tm = 32ll * v->mb * v->rg;
@@ -114,6 +116,7 @@ static int run(const mcf_problem *p, int softmax, float scale, const void *A, co
     k.m_tiles = (int32_t)m_tiles;
     k.n_blocks = (int32_t)(p->batch * m_tiles);
     k.c1 = 1.0f; k.a_mode = 0;
+    k.k_chunks = (int32_t)(p->K / v->K);
     if (softmax) {
         // exp(scale*s - max) = exp2(|scale|*log2(e) * (s' - max')) with s' = +-s; a zero scale
         // makes every logit equal, which is what A := 0 gives.

@@ -39,20 +39,27 @@ constexpr int combine_bytes(int L, int mb, int rg, int ns) {
 }
 // Staging tiles of the E store: 2 KiB (32 rows x 64 bytes) per owned block and wave.
 constexpr int estage_bytes(int L, int mb, int rg, int ns) { return rg * ns * blocks_per_wave(L, mb, ns) * 2048; }
+// Kernels with a k loop inside the block (T_K < K; `K` below is then the chunk T_K): the ring
+// carries two kinds of items, an A chunk + B chunk (tm x T_K, T_K x tn) per k step and the D
+// tile once per n-tile; a slot is as large as the larger of the two.
+constexpr int ksplit_slot_bytes(int TK, int L, int mb, int rg, int tn) {
+    const int ab = a_tile_bytes(TK, mb, rg) + b_tile_bytes(TK, tn), d = d_tile_bytes(L, tn);
+    return ab > d ? ab : d;
+}
 // `stages` ring buffers of one B + D tile each; the A tile is staged in the last ring slot
 // (it is consumed before that slot is first filled); after the loop the ring space is reused
 // by the combine scratch followed by the staging tiles of the E store.
-constexpr int total_lds_bytes(int K, int L, int mb, int rg, int ns, int nj, int stages) {
+constexpr int total_lds_bytes(int K, int L, int mb, int rg, int ns, int nj, int stages, bool ksplit = false) {
     const int st = stage_bytes(K, L, 32 * ns * nj);
     const int a = a_tile_bytes(K, mb, rg);
-    int s = (stages - 1) * st + (a > st ? a : st);
+    int s = ksplit ? stages * ksplit_slot_bytes(K, L, mb, rg, 32 * ns * nj) : (stages - 1) * st + (a > st ? a : st);
     const int c = combine_bytes(L, mb, rg, ns) + estage_bytes(L, mb, rg, ns);
     return s > c ? s : c;
 }
 // Largest ring depth (2..4) that keeps a block within `budget` bytes of LDS.
-constexpr int pick_stages(int K, int L, int mb, int rg, int ns, int nj, int budget) {
+constexpr int pick_stages(int K, int L, int mb, int rg, int ns, int nj, int budget, bool ksplit = false) {
     int s = 4;
-    while (s > 2 && total_lds_bytes(K, L, mb, rg, ns, nj, s) > budget) --s;
+    while (s > 2 && total_lds_bytes(K, L, mb, rg, ns, nj, s, ksplit) > budget) --s;
     return s;
 }
 
@@ -62,11 +69,13 @@ constexpr int pick_stages(int K, int L, int mb, int rg, int ns, int nj, int budg
 constexpr int kLdsRingBudget = 80 * 1024;
 // Softmax chains in blocks of 8 waves run their two wave groups a phase apart, which keeps two
 // n-tiles live: their ring is at least 3 deep.
-constexpr bool skewed_groups(int rg, int ns, bool softmax) { return softmax && rg * ns == 8; }
-constexpr int ring_stages(int K, int L, int mb, int rg, int ns, int nj, bool softmax) {
+constexpr bool skewed_groups(int rg, int ns, bool softmax, bool ksplit = false) { return softmax && rg * ns == 8 && !ksplit; }
+constexpr int ring_stages(int K, int L, int mb, int rg, int ns, int nj, bool softmax, bool ksplit = false) {
 #ifdef MCF_FORCE_STAGES // experiments only
     return MCF_FORCE_STAGES;
 #endif
+    // the items of a k loop are small and many: three slots keep two loads ahead of the consumer
+    if (ksplit) return total_lds_bytes(K, L, mb, rg, ns, nj, 3, true) <= 2 * kLdsRingBudget ? 3 : 2;
     const int s = pick_stages(K, L, mb, rg, ns, nj, kLdsRingBudget);
     return (skewed_groups(rg, ns, softmax) && s < 3) ? 3 : s;
 }

@@ -29,6 +29,7 @@ struct KParams {
     int32_t n_blocks;   // batch * m_tiles
     float c1;           // |scale| * log2(e) (softmax only)
     int32_t a_mode;     // 0: A as is, 1: -A (negative scale), 2: A := 0 (scale == 0)
+    int32_t k_chunks;   // kernels with a k loop: K / T_K (otherwise unused)
 };
 
 typedef int (*LaunchFn)(const KParams &p, void *stream); // returns hipError_t as int
@@ -37,6 +38,7 @@ struct Variant {
     int32_t dtype, K, L;
     int32_t mb, rg, ns, nj;
     int32_t softmax, b_kcontig;
+    int32_t ksplit;        // 1: K is the chunk T_K of a k loop inside the block; 0: T_K = K
     LaunchFn launch;
     int32_t vgprs;         // VGPRs per lane the compiler allocated (-1: unknown)
     int32_t scratch_bytes; // per-lane scratch (register spills); such variants are never picked
@@ -44,9 +46,12 @@ struct Variant {
 
 // Registry of every built kernel variant (defined in mcf_registry.cpp).
 const Variant *variants(int *count);
-// True when kernels for this (dtype, K, L) exist in the library.
-bool group_built(int dtype, int K, int L);
-const Variant *find_variant(int dtype, int K, int L, int softmax, int b_kcontig, int mb, int rg, int ns, int nj);
+// The kernel group that serves a problem's (dtype, K, L): the group with T_K = K if it is built,
+// otherwise a group with a k loop whose chunk divides K.  Returns false if there is neither;
+// *tk is the K of the group's variants, *ksplit whether they loop over k.
+bool resolve_group(int dtype, int64_t K, int64_t L, int *tk, int *ksplit);
+// Variant of that group with the given arrangement (K is the problem's K), or nullptr.
+const Variant *find_variant(int dtype, int64_t K, int64_t L, int softmax, int b_kcontig, int mb, int rg, int ns, int nj);
 
 // Layout decoded from an mcf_problem.
 struct Layout {
@@ -56,9 +61,9 @@ struct Layout {
 int decode_layout(const mcf_problem *p, Layout *out); // MCF_OK or an error status
 
 // Ring depth and LDS bytes of a variant; register estimate per lane.
-int stages_for(int K, int L, int mb, int rg, int ns, int nj, int softmax);
-int lds_bytes_for(int K, int L, int mb, int rg, int ns, int nj, int stages);
-int vgpr_estimate(int K, int L, int mb, int rg, int ns, int nj, int softmax);
+int stages_for(const Variant *v);
+int lds_bytes_for(const Variant *v);
+int vgpr_estimate(int K, int L, int mb, int rg, int ns, int nj, int softmax, int ksplit);
 
 // Feasible candidates for a problem, with their model terms, in registry order (the set
 // mcf_pick_tiles chooses from).  MCF_OK, or the status mcf_pick_tiles would return.

@@ -34,10 +34,12 @@
 
 namespace mcf {
 
-int stages_for(int K, int L, int mb, int rg, int ns, int nj, int softmax) {
-    return ring_stages(K, L, mb, rg, ns, nj, softmax != 0);
+int stages_for(const Variant *v) {
+    return ring_stages(v->K, v->L, v->mb, v->rg, v->ns, v->nj, v->softmax != 0, v->ksplit != 0);
 }
-int lds_bytes_for(int K, int L, int mb, int rg, int ns, int nj, int stages) { return total_lds_bytes(K, L, mb, rg, ns, nj, stages); }
+int lds_bytes_for(const Variant *v) {
+    return total_lds_bytes(v->K, v->L, v->mb, v->rg, v->ns, v->nj, stages_for(v), v->ksplit != 0);
+}
 
 // Registers per lane (eq. (1) restricted to the register-resident tiles, in 32-bit registers):
 // A tile (mb * K/16 operands of 4), E accumulators (mb * L/32 * 16), nj C accumulators and
@@ -46,8 +48,11 @@ int lds_bytes_for(int K, int L, int mb, int rg, int ns, int nj, int stages) { re
 // addresses and softmax state.  It tracks the compiler's allocation to within about 25 %;
 // the compiler's own numbers (scratch use) are the final arbiter, as PTX lowering is in
 // Sec. VI-D1 of the paper.
-int vgpr_estimate(int K, int L, int mb, int rg, int ns, int nj, int softmax) {
-    const int loads = (stage_bytes(K, L, 32 * ns * nj) / 1024 + rg * ns - 1) / (rg * ns);
+// (With a k loop K is the chunk: the A operands of one chunk are what a lane holds, and there
+// are two sets of load offsets, for the A + B chunk and for the D tile.)
+int vgpr_estimate(int K, int L, int mb, int rg, int ns, int nj, int softmax, int ksplit) {
+    const int slot = ksplit ? ksplit_slot_bytes(K, L, mb, rg, 32 * ns * nj) : stage_bytes(K, L, 32 * ns * nj);
+    const int loads = (ksplit ? 2 : 1) * ((slot / 1024 + rg * ns - 1) / (rg * ns));
     return mb * (K / 16) * 4 + mb * (L / 32) * 16 + nj * mb * (16 + 8) + (K / 16) * 4 + (L / 32) * 8 + loads + 24 +
            (softmax ? 16 : 0);
 }
@@ -69,11 +74,11 @@ static void eval_model(const mcf_problem *p, int softmax, const Variant *v, mcf_
     const int mb = v->mb, rg = v->rg, ns = v->ns, nj = v->nj;
     memset(t, 0, sizeof(*t));
     t->mb = mb; t->rg = rg; t->ns = ns; t->nj = nj;
-    t->tm = 32 * mb * rg; t->tn = 32 * ns * nj; t->tk = (int32_t)p->K; t->tl = (int32_t)p->L;
+    t->tm = 32 * mb * rg; t->tn = 32 * ns * nj; t->tk = v->K; t->tl = (int32_t)p->L;
     t->waves = rg * ns;
-    t->stages = stages_for((int)p->K, (int)p->L, mb, rg, ns, nj, softmax);
-    t->lds_bytes = lds_bytes_for((int)p->K, (int)p->L, mb, rg, ns, nj, t->stages);
-    t->vgpr_est = vgpr_estimate((int)p->K, (int)p->L, mb, rg, ns, nj, softmax);
+    t->stages = stages_for(v);
+    t->lds_bytes = lds_bytes_for(v);
+    t->vgpr_est = vgpr_estimate(v->K, v->L, mb, rg, ns, nj, softmax, v->ksplit);
     t->vgpr_used = v->vgprs;
     t->scratch_bytes = v->scratch_bytes;
     const int64_t es = 2; // bytes per element, fp16 / bf16
@@ -82,12 +87,14 @@ static void eval_model(const mcf_problem *p, int softmax, const Variant *v, mcf_
     // N_block of eq. (5) counted in waves, against the machine's wave slots (below)
     const int64_t units = t->blocks * t->waves;
     t->compulsory_bytes = es * p->batch * (p->M * p->K + p->K * p->N + p->N * p->L + p->M * p->L);
-    const int64_t la = (int64_t)t->tm * p->K * es * p->batch * m;
-    const int64_t lb = (int64_t)p->K * t->tn * es * p->batch * m * n;
+    // with a live k loop (T_K < K) inside n, L_A is no longer hoisted out of n: trips m * n * k
+    const int64_t k = (p->K + t->tk - 1) / t->tk;
+    const int64_t la = (int64_t)t->tm * t->tk * es * p->batch * m * (k > 1 ? n * k : 1);
+    const int64_t lb = (int64_t)t->tk * t->tn * es * p->batch * m * n * k;
     const int64_t ld = (int64_t)t->tn * p->L * es * p->batch * m * n;
     const int64_t se = (int64_t)t->tm * p->L * es * p->batch * m;
     t->model_bytes = la + lb + ld + se;
-    t->flops = (2 * (int64_t)t->tm * t->tn * p->K + 2 * (int64_t)t->tm * t->tn * p->L) * p->batch * m * n;
+    t->flops = (2 * (int64_t)t->tm * t->tn * t->tk * k + 2 * (int64_t)t->tm * t->tn * p->L) * p->batch * m * n;
     const int64_t reread = t->model_bytes > t->compulsory_bytes ? t->model_bytes - t->compulsory_bytes : 0;
     t->t_mem_s = (double)t->compulsory_bytes / kHbmBytesPerSec + (double)reread / kL2BytesPerSec;
     t->t_comp_s = (double)t->flops / kMfmaFlopsPerSec;
@@ -126,11 +133,12 @@ using namespace mcf;
 extern "C" int mcf_list_variants(const mcf_problem *p, int softmax, int32_t *out, int cap) {
     Layout lay;
     if (check_problem(p, &lay) != MCF_OK) return 0;
-    int n = 0, total = 0;
+    int n = 0, total = 0, tk = 0, ksplit = 0;
+    if (!resolve_group(p->in_dtype, p->K, p->L, &tk, &ksplit)) return 0;
     const Variant *v = variants(&n);
     for (int i = 0; i < n; ++i) {
-        if (v[i].dtype != p->in_dtype || v[i].K != p->K || v[i].L != p->L || v[i].softmax != (softmax != 0) ||
-            v[i].b_kcontig != lay.b_kcontig)
+        if (v[i].dtype != p->in_dtype || v[i].K != tk || v[i].ksplit != ksplit || v[i].L != p->L ||
+            v[i].softmax != (softmax != 0) || v[i].b_kcontig != lay.b_kcontig)
             continue;
         if (out && total < cap) {
             out[4 * total] = v[i].mb; out[4 * total + 1] = v[i].rg; out[4 * total + 2] = v[i].ns; out[4 * total + 3] = v[i].nj;
@@ -146,7 +154,7 @@ extern "C" int mcf_eval_tiles(const mcf_problem *p, int softmax, mcf_tiles *t) {
     int st = check_problem(p, &lay);
     if (st != MCF_OK) return st;
     const int mb = t->mb, rg = t->rg, ns = t->ns, nj = t->nj > 0 ? t->nj : 1;
-    const Variant *v = find_variant(p->in_dtype, (int)p->K, (int)p->L, softmax != 0, lay.b_kcontig, mb, rg, ns, nj);
+    const Variant *v = find_variant(p->in_dtype, p->K, p->L, softmax != 0, lay.b_kcontig, mb, rg, ns, nj);
     if (!v) return MCF_EUNSUPPORTED;
     eval_model(p, softmax != 0, v, t);
     return feasible(*t) ? MCF_OK : MCF_EINVAL;
@@ -159,13 +167,14 @@ int mcf::feasible_candidates(const mcf_problem *p, int softmax, std::vector<mcf_
     Layout lay;
     int st = check_problem(p, &lay);
     if (st != MCF_OK) return st;
-    int n = 0;
+    int n = 0, tk = 0, ksplit = 0;
+    if (!resolve_group(p->in_dtype, p->K, p->L, &tk, &ksplit)) return MCF_EUNSUPPORTED;
     const Variant *v = variants(&n);
     for (int pass = 0; pass < 2; ++pass) {
         out->clear();
         for (int i = 0; i < n; ++i) {
-            if (v[i].dtype != p->in_dtype || v[i].K != p->K || v[i].L != p->L || v[i].softmax != (softmax != 0) ||
-                v[i].b_kcontig != lay.b_kcontig)
+            if (v[i].dtype != p->in_dtype || v[i].K != tk || v[i].ksplit != ksplit || v[i].L != p->L ||
+                v[i].softmax != (softmax != 0) || v[i].b_kcontig != lay.b_kcontig)
                 continue;
             mcf_tiles t;
             eval_model(p, softmax != 0, &v[i], &t);

@@ -7,13 +7,14 @@ namespace mcf {
 
 #define MCF_GROUPS(X)                                                                                      \
     X(f16_32_32) X(f16_64_64) X(f16_128_128) X(f16_64_128) X(f16_128_64) X(f16_64_256) X(f16_256_256)         \
-    X(bf16_32_32) X(bf16_64_64) X(bf16_128_128) X(bf16_64_128) X(bf16_128_64) X(bf16_64_256) X(bf16_256_256)
+    X(bf16_32_32) X(bf16_64_64) X(bf16_128_128) X(bf16_64_128) X(bf16_128_64) X(bf16_64_256) X(bf16_256_256)      \
+    X(f16_k128x_64) X(f16_k128x_128) X(f16_k128x_256) X(bf16_k128x_64) X(bf16_k128x_128) X(bf16_k128x_256)
 #define MCF_DECL(NAME) const Variant *variants_##NAME(int *count);
 MCF_GROUPS(MCF_DECL)
 
 // Registers / scratch of every kernel as the compiler built it (generated at build time).
 struct Resources {
-    int dtype, K, L, mb, rg, ns, nj, softmax, b_kcontig, vgprs, sgprs, scratch_bytes;
+    int dtype, K, L, mb, rg, ns, nj, softmax, b_kcontig, ksplit, vgprs, sgprs, scratch_bytes;
 };
 static const Resources kResources[] = {
 #include "mcf_resources.inc"
@@ -35,7 +36,7 @@ static const std::vector<Variant> &all() {
             v.scratch_bytes = 0;
             for (const Resources &r : kResources)
                 if (r.dtype == v.dtype && r.K == v.K && r.L == v.L && r.mb == v.mb && r.rg == v.rg && r.ns == v.ns &&
-                    r.nj == v.nj && r.softmax == v.softmax && r.b_kcontig == v.b_kcontig) {
+                    r.nj == v.nj && r.softmax == v.softmax && r.b_kcontig == v.b_kcontig && r.ksplit == v.ksplit) {
                     v.vgprs = r.vgprs;
                     v.scratch_bytes = r.scratch_bytes;
                 }
@@ -51,16 +52,27 @@ const Variant *variants(int *count) {
     return t.data();
 }
 
-bool group_built(int dtype, int K, int L) {
-    for (const Variant &v : all())
-        if (v.dtype == dtype && v.K == K && v.L == L) return true;
-    return false;
+bool resolve_group(int dtype, int64_t K, int64_t L, int *tk, int *ksplit) {
+    int best = 0;
+    for (const Variant &v : all()) {
+        if (v.dtype != dtype || v.L != L) continue;
+        if (!v.ksplit && v.K == K) {
+            *tk = v.K; *ksplit = 0;
+            return true;
+        }
+        if (v.ksplit && K > v.K && K % v.K == 0 && v.K > best) best = v.K; // the largest chunk that divides K
+    }
+    if (!best) return false;
+    *tk = best; *ksplit = 1;
+    return true;
 }
 
-const Variant *find_variant(int dtype, int K, int L, int softmax, int b_kcontig, int mb, int rg, int ns, int nj) {
+const Variant *find_variant(int dtype, int64_t K, int64_t L, int softmax, int b_kcontig, int mb, int rg, int ns, int nj) {
+    int tk = 0, ksplit = 0;
+    if (!resolve_group(dtype, K, L, &tk, &ksplit)) return nullptr;
     for (const Variant &v : all())
-        if (v.dtype == dtype && v.K == K && v.L == L && v.softmax == softmax && v.b_kcontig == b_kcontig &&
-            v.mb == mb && v.rg == rg && v.ns == ns && v.nj == nj)
+        if (v.dtype == dtype && v.K == tk && v.L == L && v.ksplit == ksplit && v.softmax == softmax &&
+            v.b_kcontig == b_kcontig && v.mb == mb && v.rg == rg && v.ns == ns && v.nj == nj)
             return &v;
     return nullptr;
 }

@@ -62,7 +62,7 @@ def test_validation_codes_without_a_launch():
     assert lib.mcf_pick_tiles(ctypes.byref(make_problem(2, 64, 16, 64, 16, "f16")), 0, ctypes.byref(t)) == 2
 
 
-_BUILT_PAPER_SHAPES = [n for n in mi.PAPER_SHAPES if n not in ("G5", "G6", "S6")]
+_BUILT_PAPER_SHAPES = [n for n in mi.PAPER_SHAPES if n != "S6"]
 
 
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"] + _BUILT_PAPER_SHAPES)
@@ -73,13 +73,14 @@ def test_picker_terms_match_the_paper_model(name):
     w = mi.WORKLOADS[name] if name in mi.WORKLOADS else mi.PAPER_SHAPES[name]
     prob = _c_problem(w)
     shapes = mcf.list_variants(prob, w.softmax)
-    assert len(shapes) >= (8 if w.K * w.L <= 128 * 128 else 4)
+    assert len(shapes) >= (8 if w.K * w.L <= 128 * 128 else 3)
     dims = {"m": w.M, "n": w.N, "k": w.K, "h": w.L}
     best = None
     for (mb, rg, ns, nj) in shapes:
         t = mcf.eval_tiles(prob, mb, rg, ns, nj, softmax=w.softmax)
-        assert (t.tm, t.tn, t.tk, t.tl, t.waves) == (32 * mb * rg, 32 * ns * nj, w.K, w.L, rg * ns)
-        tiles = {"m": t.tm, "n": t.tn, "k": w.K, "h": w.L}
+        assert (t.tm, t.tn, t.tl, t.waves) == (32 * mb * rg, 32 * ns * nj, w.L, rg * ns)
+        assert t.tk == (w.K if w.K <= 256 else 128)
+        tiles = {"m": t.tm, "n": t.tn, "k": t.tk, "h": w.L}
         units_per_block = (t.waves + 3) // 4
         # eq. (5) in waves: N_block = blocks x waves, N_SM = wave slots of the machine
         r = pm.estimate("mhnk", dims, tiles, w.batch, 2, W=W_HBM, P=P_MFMA, n_units=WAVE_SLOTS / t.waves,
@@ -96,7 +97,11 @@ def test_picker_terms_match_the_paper_model(name):
         bd = pm.shm_estm(tiles, "BD") * 2
         a = pm.tile_elems("A", tiles) * 2
         assert 2 <= t.stages <= 4
-        assert t.lds_bytes >= (t.stages - 1) * bd + max(bd, a)
+        if t.tk < w.K:   # k loop: a ring slot holds the A + B chunk of a k step or the D tile
+            ab = (pm.tile_elems("A", tiles) + pm.tile_elems("B", tiles)) * 2
+            assert t.lds_bytes >= t.stages * max(ab, pm.tile_elems("D", tiles) * 2)
+        else:
+            assert t.lds_bytes >= (t.stages - 1) * bd + max(bd, a)
         ok = (t.lds_bytes <= LDS_MAX and t.scratch_bytes == 0 and t.vgpr_est <= 512 // units_per_block
               and pm.padding_ok(w.M, t.tm) and pm.padding_ok(w.N, t.tn))
         assert ok == (t.feasible and pm.padding_ok(w.M, t.tm) and pm.padding_ok(w.N, t.tn))
@@ -109,14 +114,20 @@ def test_picker_terms_match_the_paper_model(name):
     assert pm.padding_ok(w.M, picked.tm) and pm.padding_ok(w.N, picked.tn)
 
 
-def test_paper_shapes_without_kernels_are_refused():
-    """K = 512 / 1024 (G5, G6: they need a k loop inside the block) and K = H = 80 (S6) have
-    no built kernels: the picker says so instead of returning something that cannot run."""
+def test_shapes_without_kernels_are_refused():
+    """K = H = 80 (S6) and other (K, L) no group covers have no built kernels: the picker says
+    so instead of returning something that cannot run.  K = 512, 1024 (G5, G6) are served by
+    the kernels with a k loop of T_K = 128."""
     lib = mcf.load_library()
-    for name in ("G5", "G6", "S6"):
+    t = Tiles()
+    w = mi.PAPER_SHAPES["S6"]
+    assert lib.mcf_pick_tiles(ctypes.byref(_c_problem(w)), int(w.softmax), ctypes.byref(t)) == 2
+    assert lib.mcf_pick_tiles(ctypes.byref(make_problem(1, 512, 192, 512, 64, "f16")), 0, ctypes.byref(t)) == 2  # 192 = 1.5 chunks
+    assert lib.mcf_pick_tiles(ctypes.byref(make_problem(1, 512, 512, 512, 32, "f16")), 0, ctypes.byref(t)) == 2  # no k-loop group with L = 32
+    for name in ("G5", "G6"):
         w = mi.PAPER_SHAPES[name]
-        t = Tiles()
-        assert lib.mcf_pick_tiles(ctypes.byref(_c_problem(w)), int(w.softmax), ctypes.byref(t)) == 2, name
+        assert lib.mcf_pick_tiles(ctypes.byref(_c_problem(w)), 0, ctypes.byref(t)) == 0
+        assert (t.tk, t.tl) == (128, 256) and t.tk < w.K
 
 
 def test_register_estimate_tracks_the_compiler():
