@@ -12,7 +12,10 @@ constexpr double kHbmBytesPerSec = 8.0e12;    // W: HBM3E peak
 constexpr double kL2BytesPerSec = 32.0e12;    // bandwidth charged to re-reads served by L2/MALL
 constexpr double kMfmaFlopsPerSec = 2.5e15;   // P: dense fp16/bf16 MFMA peak
 constexpr int kComputeUnits = 256;            // compute units
-constexpr int kWaveSlots = kComputeUnits * 4 * 2; // N_SM of eq. (5): two waves on each of the 4 SIMDs of a CU
+// eq. (5) in waves: a block counts with its waves, but at most 6 (measured: on one compute unit a
+// block of 8 waves delivers about 1.5x a block of 4, not 2x), and N_SM is 6 such units per CU.
+constexpr int kWaveUnitsPerBlock = 6;
+constexpr int kWaveUnits = kComputeUnits * kWaveUnitsPerBlock;
 constexpr int kLdsBytesPerBlock = 160 * 1024; // Shm_max of Rule 4
 constexpr int kVgprBudget = 512;              // arch + accumulation VGPRs per lane at 1 wave/SIMD
 

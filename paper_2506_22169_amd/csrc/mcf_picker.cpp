@@ -21,9 +21,9 @@
 //     holds a ring of 2..4 (B tile + D tile) stages, as deep as fits 80 KiB so that two
 //     blocks share a compute unit.
 //   * eq. (5) counts parallel work against parallel hardware.  Here the unit is the wave:
-//     N_block := blocks x waves per block, N_SM := 256 compute units x 4 SIMDs x 2 wave slots
-//     (two waves per SIMD is what it takes to overlap the matrix pipe with LDS / VALU work;
-//     measured).  A block of 8 waves therefore counts twice a block of 4.
+//     N_block := blocks x min(waves per block, 6), N_SM := 256 compute units x 6.  A second wave
+//     per SIMD overlaps the matrix pipe with LDS / VALU work, but a block of 8 waves measures
+//     about 1.5x the throughput of a block of 4 on one compute unit, not 2x: hence the cap.
 #include <math.h>
 #include <string.h>
 
@@ -85,7 +85,7 @@ static void eval_model(const mcf_problem *p, int softmax, const Variant *v, mcf_
     const int64_t m = (p->M + t->tm - 1) / t->tm, n = (p->N + t->tn - 1) / t->tn;
     t->blocks = p->batch * m;
     // N_block of eq. (5) counted in waves, against the machine's wave slots (below)
-    const int64_t units = t->blocks * t->waves;
+    const int64_t units = t->blocks * (t->waves < kWaveUnitsPerBlock ? t->waves : kWaveUnitsPerBlock);
     t->compulsory_bytes = es * p->batch * (p->M * p->K + p->K * p->N + p->N * p->L + p->M * p->L);
     // with a live k loop (T_K < K) inside n, L_A is no longer hoisted out of n: trips m * n * k
     const int64_t k = (p->K + t->tk - 1) / t->tk;
@@ -98,7 +98,7 @@ static void eval_model(const mcf_problem *p, int softmax, const Variant *v, mcf_
     const int64_t reread = t->model_bytes > t->compulsory_bytes ? t->model_bytes - t->compulsory_bytes : 0;
     t->t_mem_s = (double)t->compulsory_bytes / kHbmBytesPerSec + (double)reread / kL2BytesPerSec;
     t->t_comp_s = (double)t->flops / kMfmaFlopsPerSec;
-    t->alpha = units > 0 ? (double)(units + kWaveSlots) / (double)units : 1.0;
+    t->alpha = units > 0 ? (double)(units + kWaveUnits) / (double)units : 1.0;
     t->t_est_s = (t->t_mem_s + t->t_comp_s) * t->alpha;
 }
 
