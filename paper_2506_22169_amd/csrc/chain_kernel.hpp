@@ -297,19 +297,37 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             const int64_t k0 = (int64_t)r * KD;
             const void *abase = uniform((const void *)(Ag + k0));
             const void *bbase = uniform((const void *)(BKC ? Bg + (int64_t)nt0 * sb_r + k0 : Bg + k0 * sb_r + nt0));
+            if (!ragged) {
 #pragma unroll
-            for (int u = 0; u < P; ++u) {
-                const int j = wave + u * W; // wave-uniform
-                const int jj = j < CAB ? j : CAB - 1;
-                dma16(dst0 + (jj - wave) * 1024, ragged ? ks_offset(false, u, nt0, true) : voff[u], jj < CA ? abase : bbase);
+                for (int u = 0; u < P; ++u) {
+                    const int j = wave + u * W; // wave-uniform
+                    const int jj = j < CAB ? j : CAB - 1;
+                    dma16(dst0 + (jj - wave) * 1024, voff[u], jj < CA ? abase : bbase);
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < P; ++u) {
+                    const int j = wave + u * W;
+                    const int jj = j < CAB ? j : CAB - 1;
+                    dma16(dst0 + (jj - wave) * 1024, ks_offset(false, u, nt0, true), jj < CA ? abase : bbase);
+                }
             }
         } else {
             const void *dbase = uniform((const void *)(Dg + (int64_t)nt0 * sd_r));
+            if (!ragged) {
 #pragma unroll
-            for (int u = 0; u < P; ++u) {
-                const int j = wave + u * W;
-                const int jj = j < CD ? j : CD - 1;
-                dma16(dst0 + (jj - wave) * 1024, ragged ? ks_offset(true, u, nt0, true) : voff_d[u], dbase);
+                for (int u = 0; u < P; ++u) {
+                    const int j = wave + u * W;
+                    const int jj = j < CD ? j : CD - 1;
+                    dma16(dst0 + (jj - wave) * 1024, voff_d[u], dbase);
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < P; ++u) {
+                    const int j = wave + u * W;
+                    const int jj = j < CD ? j : CD - 1;
+                    dma16(dst0 + (jj - wave) * 1024, ks_offset(true, u, nt0, true), dbase);
+                }
             }
         }
     };
@@ -566,7 +584,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             if (n_items - q >= S - 1) wait_vm<(S - 2) * P>();
             else wait_vm<0>();
             __syncthreads(); // item q is complete for every wave; the slot of item q-1 is free
-            if (q + S - 1 < n_items) {
+            if (q + S - 1 < n_items && !(MCF_ABLATE & 32)) {
                 issue_item(lt, lr, stage_l);
                 if (++lr == NI) { lr = 0; ++lt; }
                 stage_l = stage_l + 1 == S ? 0 : stage_l + 1;
@@ -575,7 +593,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             if (n0 < N) {
                 const unsigned st = stage_c * STAGE;
                 if (cr < KC) {
-                    load_a(st + A_LDS);
+                    if (!(MCF_ABLATE & 64)) load_a(st + A_LDS);
                     phase_g1(st, cr == 0);
                 } else {
                     phase_g2_prefetch(st);

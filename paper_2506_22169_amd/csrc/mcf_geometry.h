@@ -74,8 +74,9 @@ constexpr int ring_stages(int K, int L, int mb, int rg, int ns, int nj, bool sof
 #ifdef MCF_FORCE_STAGES // experiments only
     return MCF_FORCE_STAGES;
 #endif
-    // the items of a k loop are small and many: three slots keep two loads ahead of the consumer
-    if (ksplit) return total_lds_bytes(K, L, mb, rg, ns, nj, 3, true) <= 2 * kLdsRingBudget ? 3 : 2;
+    // the items of a k loop are small and many, and the shapes that need one rarely fill the
+    // machine: as deep as the whole LDS allows, to keep as many loads in flight as possible
+    if (ksplit) return pick_stages(K, L, mb, rg, ns, nj, 2 * kLdsRingBudget, true);
     const int s = pick_stages(K, L, mb, rg, ns, nj, kLdsRingBudget);
     return (skewed_groups(rg, ns, softmax) && s < 3) ? 3 : s;
 }

@@ -32,6 +32,8 @@
     X(1, 4, 1, 1)            \
     X(1, 2, 2, 1)            \
     X(1, 1, 4, 1)            \
+    X(1, 1, 2, 1)            \
+    X(1, 1, 2, 2)            \
     X(1, 4, 2, 1)            \
     X(1, 2, 2, 2)            \
     X(1, 1, 4, 2)            \
