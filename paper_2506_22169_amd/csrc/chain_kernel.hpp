@@ -48,6 +48,9 @@
 #endif
 // Compile-time ablation mask for experiments (0 in the library): 1 no operand reads from LDS,
 // 2 no MFMA, 4 no combine, 8 no E store, 16 no barrier in the loop, 32 no loads in the loop.
+#ifndef MCF_LAZY_MAX
+#define MCF_LAZY_MAX 8
+#endif
 #ifndef MCF_ABLATE
 #define MCF_ABLATE 0
 #endif
@@ -526,7 +529,13 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
 #pragma unroll
                     for (int r = 0; r < 16; ++r) mx = fmaxf(mx, accC[j][mb][r]);
                 mx = xhalf_max(mx);
-                const float m_new = fmaxf(m_run[mb], mx);
+                // The running maximum only has to keep the exponentials in range, not to be exact:
+                // it follows the row maximum only when that has grown by more than
+                // MCF_LAZY_MAX in the exponent (so p <= 2^MCF_LAZY_MAX), which after the first
+                // tiles is rare -- and with it the rescaling of the accumulators below.  The
+                // result is the same up to rounding: numerator and denominator share m.
+                float m_new = fmaxf(m_run[mb], mx);
+                if (MCF_LAZY_MAX > 0) m_new = (m_new - m_run[mb]) * c1 > (float)MCF_LAZY_MAX ? m_new : m_run[mb];
                 const float corr = __builtin_amdgcn_exp2f((m_run[mb] - m_new) * c1);
                 const float mneg = -m_new * c1;
                 float sum = 0.f;
