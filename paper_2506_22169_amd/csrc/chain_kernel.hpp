@@ -132,13 +132,15 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     constexpr int W = RG * NS;           // waves per block
     constexpr int TM = 32 * MB * RG;     // rows per block
     constexpr int TN = 32 * NS * NJ;     // columns per n-iteration
+    static_assert(KD % 16 == 0 && LD % 8 == 0, "K in MFMA k-steps of 16, L in 16-byte pieces");
     constexpr int KS = KD / 16;          // MFMA k-steps of GEMM 1
-    constexpr int HB = LD / 32;          // 32-wide h blocks of GEMM 2
+    constexpr int HB = h_blocks(LD);     // 32-wide h blocks of GEMM 2 (the last may be partial)
+    constexpr int KCH = KD / 8, LCH = LD / 8;                  // 16-byte chunks in a row of K / L elements
+    constexpr bool KPAD = pitch_elems(KD) != KD, LPAD = pitch_elems(LD) != LD; // rows padded to a power-of-two pitch
     constexpr int S = ring_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX, KSPLIT); // depth of the LDS ring
-    constexpr int RBA = 2 * KD;                  // row bytes of the A tile (rows m)
-    constexpr int RBB = BKC ? 2 * KD : 2 * TN;   // row bytes of the B tile (rows n / rows k)
-    constexpr int RBD = 2 * LD;                  // row bytes of the D tile (rows n)
-    constexpr int RBE = 2 * LD;                  // row bytes of the E staging tile (rows m)
+    constexpr int RBA = 2 * pitch_elems(KD);                // row bytes of the A tile (rows m)
+    constexpr int RBB = BKC ? 2 * pitch_elems(KD) : 2 * TN; // row bytes of the B tile (rows n / rows k)
+    constexpr int RBD = 2 * pitch_elems(LD);                // row bytes of the D tile (rows n)
     constexpr int B_BYTES = b_tile_bytes(KD, TN);
     constexpr int A_BYTES = a_tile_bytes(KD, MB, RG);
     // Without a k loop a ring slot holds [B tile | D tile] and the A tile borrows the last slot
@@ -204,9 +206,11 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             int row = slot / (RBB / 16), ch = slot % (RBB / 16);
             if (BKC) {
                 ch ^= swz_b128(RBB, row);
+                if (KPAD && ch >= KCH) ch = 0; // padding of the row: any valid piece
                 if (clamp && nt0 + row >= N) row = N - 1 - nt0;
             } else {
                 ch ^= swz_tr(RBB, row);
+                if (KPAD && row >= KD) row = 0; // rows k beyond K: any valid row
                 if (clamp && nt0 + 8 * ch >= N) ch = 0;
             }
             return (unsigned)(row * sb_r * 2 + ch * 16);
@@ -214,6 +218,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             const int slot = 64 * (j - CB) + lane;
             int row = slot / (RBD / 16), ch = slot % (RBD / 16);
             ch ^= swz_tr(RBD, row);
+            if (LPAD && ch >= LCH) ch = 0;
             if (clamp && nt0 + row >= N) row = N - 1 - nt0;
             return (unsigned)(row * sd_r * 2 + ch * 16);
         }
@@ -262,6 +267,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             const int slot = 64 * j + lane;
             int row = slot / (RBD / 16), ch = slot % (RBD / 16);
             ch ^= swz_tr(RBD, row);
+            if (LPAD && ch >= LCH) ch = 0;
             if (clamp && nt0 + row >= N) row = N - 1 - nt0;
             return (unsigned)(row * sd_r * 2 + ch * 16);
         }
@@ -346,6 +352,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             const int slot = 64 * jj + lane;
             int row = slot / (RBA / 16), ch = slot % (RBA / 16);
             ch ^= swz_b128(RBA, row);
+            if (KPAD && ch >= KCH) ch = 0;             // padding of the row: any valid piece
             if (mrow0 + row >= M) row = M - 1 - mrow0; // rows past M: any valid row, never stored
             dma16(dst0 + (jj - wave) * 1024, (unsigned)(row * sa_r * 2 + ch * 16), abase);
         }
@@ -803,11 +810,13 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     // 16-byte pieces of a row: a store instruction writes whole row segments (whole rows when
     // the wave owns all h blocks of its rows).
     if (blk0 < NBLK) {
+        static_assert(combine_runs_ok(LD, MB, NS), "a wave's run of blocks straddles row sets");
         constexpr int HPW = BPW < HB ? BPW : HB;    // h blocks per owned row set
         constexpr int MPW = BPW < HB ? 1 : BPW / HB; // row sets (of 32 rows) owned
-        constexpr int RBS = HPW * 64;                // staged row bytes
+        constexpr int RBS = estage_row_bytes(LD, MB, NS); // staged row bytes: HPW * 64, rounded up to a power of two
+        constexpr bool EPAD = RBS != HPW * 64 || LPAD; // some staged pieces are padding or lie beyond L
         const int mb0 = blk0 / HB, h0 = blk0 % HB;
-        lds_u8 *es = smem + combine_bytes(LD, MB, RG, NS) + wave * (BPW * 2048);
+        lds_u8 *es = smem + combine_bytes(LD, MB, RG, NS) + wave * estage_wave_bytes(LD, MB, NS);
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             const float inv = SOFTMAX ? 1.0f / l_run[mb] : 1.0f;
@@ -838,6 +847,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             const int row = slot / CPR;
             const int ch = (slot % CPR) ^ swz_b128(RBS, row);
             const u32x4 v = *(const lds_u32x4 *)(es + 16 * slot);
+            if (EPAD && (ch >= 4 * HPW || 32 * h0 + 8 * ch >= LD)) continue;
             if (rbase + row < M && (!(MCF_ABLATE & 8) || v[0] == 0x12345u))
                 *(u32x4 *)(Eg + (int64_t)(rbase + row) * se_r + 32 * h0 + 8 * ch) = v;
         }
@@ -861,10 +871,12 @@ int launch_chain(const KParams &p, void *stream) {
 }
 
 // Launcher of an instantiation, or nullptr when the wave arrangement cannot exist for this
-// (K, L): more LDS than a compute unit has.  Such kernels are not compiled at all.
+// (K, L): more LDS than a compute unit has, or (L not a multiple of 32 times a power of two) a
+// wave's run of accumulator blocks would straddle row sets.  Such kernels are not compiled.
 template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool BKC, bool KSPLIT = false>
 constexpr LaunchFn launcher_or_null() {
-    if constexpr (total_lds_bytes(KD, LD, MB, RG, NS, NJ, ring_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX, KSPLIT), KSPLIT) <= kLdsBytesPerBlock)
+    if constexpr (total_lds_bytes(KD, LD, MB, RG, NS, NJ, ring_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX, KSPLIT), KSPLIT) <= kLdsBytesPerBlock &&
+                  combine_runs_ok(LD, MB, NS))
         return &launch_chain<T, KD, LD, MB, RG, NS, NJ, SOFTMAX, BKC, KSPLIT>;
     else
         return nullptr;

@@ -21,24 +21,48 @@ constexpr int swz_tr(int row_bytes, int row) {
     return row_bytes == 64 ? 0 : row_bytes == 128 ? 4 * ((row >> 1) & 1) : 4 * (row & 3);
 }
 
-constexpr int a_tile_bytes(int K, int mb, int rg) { return 32 * mb * rg * K * 2; }
-constexpr int b_tile_bytes(int K, int tn) { return K * tn * 2; }
-constexpr int d_tile_bytes(int L, int tn) { return tn * L * 2; }
+// K and L need not be powers of two (K a multiple of 16, L of 8): rows of the LDS tiles are
+// then laid out with the next power-of-two pitch (the swizzles want one); the chunks beyond
+// K or L in a row are loaded from valid memory and never reach a result that is stored.
+constexpr int pitch_elems(int x) { return x <= 32 ? 32 : x <= 64 ? 64 : x <= 128 ? 128 : x <= 256 ? 256 : 512; }
+constexpr int h_blocks(int L) { return (L + 31) / 32; } // 32-wide column blocks of E (the last may be partial)
+
+constexpr int a_tile_bytes(int K, int mb, int rg) { return 32 * mb * rg * pitch_elems(K) * 2; }
+constexpr int b_tile_bytes(int K, int tn) { return pitch_elems(K) * tn * 2; }
+constexpr int d_tile_bytes(int L, int tn) { return tn * pitch_elems(L) * 2; }
 constexpr int stage_bytes(int K, int L, int tn) { return b_tile_bytes(K, tn) + d_tile_bytes(L, tn); }
-// Cross-wave combine when ns > 1: the mb * L/32 accumulator blocks (32 x 32 of E, 16 fp32 per
-// lane) of a row-group are dealt out to its ns waves, BPW in a row; every wave parks the
+// Cross-wave combine when ns > 1: the mb * ceil(L/32) accumulator blocks (32 x 32 of E, 16 fp32
+// per lane) of a row-group are dealt out to its ns waves, BPW in a row; every wave parks the
 // blocks it does not own and its softmax state in LDS.
-constexpr int blocks_per_wave(int L, int mb, int ns) { return (mb * (L / 32) + ns - 1) / ns; }
-// Blocks a wave parks: all but the run it owns (waves beyond the last run own none).
+constexpr int blocks_per_wave(int L, int mb, int ns) { return (mb * h_blocks(L) + ns - 1) / ns; }
+// Most blocks any wave parks: all but the run it owns; the last wave's run is the shortest
+// (empty when there are fewer blocks than waves).
 constexpr int parked_blocks(int L, int mb, int ns) {
-    const int n = mb * (L / 32);
-    return n >= ns ? n - blocks_per_wave(L, mb, ns) : n;
+    const int n = mb * h_blocks(L), bpw = blocks_per_wave(L, mb, ns);
+    const int last = n - (ns - 1) * bpw;
+    return n - (last < 0 ? 0 : last);
+}
+// A wave's run of blocks must lie within one row set of 32 rows or cover whole row sets.
+constexpr bool combine_runs_ok(int L, int mb, int ns) {
+    const int hb = h_blocks(L), bpw = blocks_per_wave(L, mb, ns);
+    return bpw >= hb ? bpw % hb == 0 : (mb == 1 || hb % bpw == 0);
 }
 constexpr int combine_bytes(int L, int mb, int rg, int ns) {
     return ns > 1 ? rg * ns * (parked_blocks(L, mb, ns) * 16 + 2 * mb) * 64 * 4 : 0;
 }
-// Staging tiles of the E store: 2 KiB (32 rows x 64 bytes) per owned block and wave.
-constexpr int estage_bytes(int L, int mb, int rg, int ns) { return rg * ns * blocks_per_wave(L, mb, ns) * 2048; }
+// Staging tile of the E store, per wave: the rows of the row sets it owns (32 each) times the
+// bytes of the h blocks it owns in a row, that pitch rounded up to a power of two.
+constexpr int estage_row_bytes(int L, int mb, int ns) {
+    const int hb = h_blocks(L), bpw = blocks_per_wave(L, mb, ns);
+    const int hpw = bpw < hb ? bpw : hb;
+    return 2 * pitch_elems(32 * hpw);
+}
+constexpr int estage_wave_bytes(int L, int mb, int ns) {
+    const int hb = h_blocks(L), bpw = blocks_per_wave(L, mb, ns);
+    const int mpw = bpw < hb ? 1 : bpw / hb;
+    return mpw * 32 * estage_row_bytes(L, mb, ns);
+}
+constexpr int estage_bytes(int L, int mb, int rg, int ns) { return rg * ns * estage_wave_bytes(L, mb, ns); }
 // Kernels with a k loop inside the block (T_K < K; `K` below is then the chunk T_K): the ring
 // carries two kinds of items, an A chunk + B chunk (tm x T_K, T_K x tn) per k step and the D
 // tile once per n-tile; a slot is as large as the larger of the two.

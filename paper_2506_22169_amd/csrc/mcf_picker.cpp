@@ -53,7 +53,8 @@ int lds_bytes_for(const Variant *v) {
 int vgpr_estimate(int K, int L, int mb, int rg, int ns, int nj, int softmax, int ksplit) {
     const int slot = ksplit ? ksplit_slot_bytes(K, L, mb, rg, 32 * ns * nj) : stage_bytes(K, L, 32 * ns * nj);
     const int loads = (ksplit ? 2 : 1) * ((slot / 1024 + rg * ns - 1) / (rg * ns));
-    return mb * (K / 16) * 4 + mb * (L / 32) * 16 + nj * mb * (16 + 8) + (K / 16) * 4 + (L / 32) * 8 + loads + 24 +
+    const int hb = h_blocks(L);
+    return mb * (K / 16) * 4 + mb * hb * 16 + nj * mb * (16 + 8) + (K / 16) * 4 + hb * 8 + loads + 24 +
            (softmax ? 16 : 0);
 }
 

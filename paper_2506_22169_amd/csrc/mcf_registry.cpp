@@ -8,7 +8,8 @@ namespace mcf {
 #define MCF_GROUPS(X)                                                                                      \
     X(f16_32_32) X(f16_64_64) X(f16_128_128) X(f16_64_128) X(f16_128_64) X(f16_64_256) X(f16_256_256)         \
     X(bf16_32_32) X(bf16_64_64) X(bf16_128_128) X(bf16_64_128) X(bf16_128_64) X(bf16_64_256) X(bf16_256_256)      \
-    X(f16_k128x_64) X(f16_k128x_128) X(f16_k128x_256) X(bf16_k128x_64) X(bf16_k128x_128) X(bf16_k128x_256)
+    X(f16_k128x_64) X(f16_k128x_128) X(f16_k128x_256) X(bf16_k128x_64) X(bf16_k128x_128) X(bf16_k128x_256)      \
+    X(f16_80_80) X(bf16_80_80)
 #define MCF_DECL(NAME) const Variant *variants_##NAME(int *count);
 MCF_GROUPS(MCF_DECL)
 

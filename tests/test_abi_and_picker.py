@@ -62,7 +62,7 @@ def test_validation_codes_without_a_launch():
     assert lib.mcf_pick_tiles(ctypes.byref(make_problem(2, 64, 16, 64, 16, "f16")), 0, ctypes.byref(t)) == 2
 
 
-_BUILT_PAPER_SHAPES = [n for n in mi.PAPER_SHAPES if n != "S6"]
+_BUILT_PAPER_SHAPES = list(mi.PAPER_SHAPES)
 
 
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"] + _BUILT_PAPER_SHAPES)
@@ -80,6 +80,7 @@ def test_picker_terms_match_the_paper_model(name):
         t = mcf.eval_tiles(prob, mb, rg, ns, nj, softmax=w.softmax)
         assert (t.tm, t.tn, t.tl, t.waves) == (32 * mb * rg, 32 * ns * nj, w.L, rg * ns)
         assert t.tk == (w.K if w.K <= 256 else 128)
+        pitch = lambda x: 1 << (x - 1).bit_length()   # LDS rows are laid out with a power-of-two pitch
         tiles = {"m": t.tm, "n": t.tn, "k": t.tk, "h": w.L}
         units_per_block = (t.waves + 3) // 4
         # eq. (5) in waves: N_block = blocks x min(waves, 6), N_SM = 256 compute units x 6
@@ -94,8 +95,9 @@ def test_picker_terms_match_the_paper_model(name):
         assert t.alpha == pytest.approx(r["alpha"], rel=1e-12)
         assert t.t_est_s == pytest.approx(r["t_estm"], rel=1e-12)
         # eq. (1), split: LDS holds `stages` copies of the B and D tiles (plus the A tile in the last slot)
-        bd = pm.shm_estm(tiles, "BD") * 2
-        a = pm.tile_elems("A", tiles) * 2
+        padded = dict(tiles, k=pitch(t.tk), h=pitch(w.L))
+        bd = pm.shm_estm(padded, "BD") * 2
+        a = pm.tile_elems("A", padded) * 2
         assert 2 <= t.stages <= 4
         if t.tk < w.K:   # k loop: a ring slot holds the A + B chunk of a k step or the D tile
             ab = (pm.tile_elems("A", tiles) + pm.tile_elems("B", tiles)) * 2
@@ -115,13 +117,12 @@ def test_picker_terms_match_the_paper_model(name):
 
 
 def test_shapes_without_kernels_are_refused():
-    """K = H = 80 (S6) and other (K, L) no group covers have no built kernels: the picker says
-    so instead of returning something that cannot run.  K = 512, 1024 (G5, G6) are served by
-    the kernels with a k loop of T_K = 128."""
+    """(K, L) that no group covers have no built kernels: the picker says so instead of
+    returning something that cannot run.  K = 512, 1024 (G5, G6) are served by the kernels
+    with a k loop of T_K = 128."""
     lib = mcf.load_library()
     t = Tiles()
-    w = mi.PAPER_SHAPES["S6"]
-    assert lib.mcf_pick_tiles(ctypes.byref(_c_problem(w)), int(w.softmax), ctypes.byref(t)) == 2
+    assert lib.mcf_pick_tiles(ctypes.byref(make_problem(16, 256, 48, 256, 48, "f16")), 1, ctypes.byref(t)) == 2
     assert lib.mcf_pick_tiles(ctypes.byref(make_problem(1, 512, 192, 512, 64, "f16")), 0, ctypes.byref(t)) == 2  # 192 = 1.5 chunks
     assert lib.mcf_pick_tiles(ctypes.byref(make_problem(1, 512, 512, 512, 32, "f16")), 0, ctypes.byref(t)) == 2  # no k-loop group with L = 32
     for name in ("G5", "G6"):
@@ -136,7 +137,7 @@ def test_register_estimate_tracks_the_compiler():
     with at most a few exceptions (the analogue of the paper's estimate-vs-lowering check)."""
     total = wrong = 0
     for dtype in ("f16", "bf16"):
-        for K, L in ((32, 32), (64, 64), (128, 128), (64, 128), (128, 64), (64, 256), (256, 256)):
+        for K, L in ((32, 32), (64, 64), (128, 128), (64, 128), (128, 64), (64, 256), (256, 256), (80, 80)):
             for softmax in (False, True):
                 prob = make_problem(4, 1024, K, 1024, L, dtype, b_stride=(1024 * K, 1, K) if softmax else None)
                 for shape in mcf.list_variants(prob, softmax):

@@ -18,7 +18,8 @@ pytestmark = pytest.mark.gpu
 @pytest.mark.parametrize("softmax", [False, True])
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 @pytest.mark.parametrize("KL", [(32, 32), (64, 64), (128, 128), (64, 128), (128, 64), (64, 256), (256, 256),
-                                (256, 64), (384, 128), (512, 256)])   # the last three: k loop inside the block
+                                (256, 64), (384, 128), (512, 256),    # these three: k loop inside the block
+                                (80, 80)])                            # rows padded to a power-of-two pitch in LDS
 def test_every_variant_small_ragged(KL, dtype, softmax):
     """Every built wave arrangement on a shape with a ragged m tail and a ragged n tail that
     spans several tiles of the largest variant (tm up to 256, tn up to 256)."""
@@ -63,11 +64,11 @@ def test_workload_full_size(name):
     print(f"{name}: max|err|/max|oracle| = {r:.3e}", flush=True)
 
 
-@pytest.mark.parametrize("name", [n for n in mi.PAPER_SHAPES if n != "S6"])
+@pytest.mark.parametrize("name", list(mi.PAPER_SHAPES))
 def test_paper_shape_tables(name):
     """The shapes of the paper's own evaluation (Table II chains, Table III attention modules)
     at full size with the picker's tiles, every element (G5, G6 with K = 512, 1024 run the
-    kernels with a k loop).  S6 (K = H = 80) has no built kernels."""
+    kernels with a k loop; S6 has K = H = 80)."""
     w = mi.PAPER_SHAPES[name]
     print(f"case {name}", flush=True)
     r = check_full(w)
@@ -176,10 +177,10 @@ def test_random_shapes_strides_and_tiles():
     wave arrangement, each compared with the oracle element by element; the padding around a
     strided output must come back untouched."""
     rng = np.random.default_rng(20250622)
-    groups = [(32, 32), (64, 64), (128, 128), (64, 128), (128, 64), (64, 256), (256, 256), (256, 128), (640, 64)]
+    groups = [(32, 32), (64, 64), (128, 128), (64, 128), (128, 64), (64, 256), (256, 256), (256, 128), (640, 64), (80, 80)]
     sizes = [1, 2, 7, 31, 32, 33, 64, 100, 129, 255, 300, 517]
     worst = 0.0
-    for case in range(64):
+    for case in range(72):
         K, L = groups[rng.integers(len(groups))]
         dtype = ("f16", "bf16")[rng.integers(2)]
         softmax = bool(rng.integers(2))

@@ -81,7 +81,7 @@ def test_defaults_and_errors():
         mcf.search_tiles(prob, False, lambda t: 1 / 0)
     # no kernels for this (K, L)
     with pytest.raises(mcf.McfError) as e:
-        mcf.search_tiles(make_problem(1, 512, 80, 512, 80, "f16"), False, lambda t: 1.0)
+        mcf.search_tiles(make_problem(1, 512, 48, 512, 48, "f16"), False, lambda t: 1.0)
     assert e.value.status == 2
     lib = mcf.load_library()
     assert lib.mcf_search_tiles(ctypes.byref(prob), 0, None, ctypes.cast(None, mcf.binding.MEASURE_FN), None, None, None) == 1
