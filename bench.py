@@ -36,7 +36,7 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="cfg2", help="cfg1..cfg5 (default: cfg2, the configuration the metric is quoted on), or a row of the "
                                                       "paper's shape tables: G1..G12, S1..S5, S7..S9")
-    ap.add_argument("--tiles", default=None, help="mb,rg,ns,nj to override the picker")
+    ap.add_argument("--tiles", default=None, help="mb,rg,ns,nj[,tl] to override the picker")
     ap.add_argument("--tune", action="store_true",
                     help="choose the tiles by the measured search (Alg. 1) before the warm-up instead of by the "
                          "model alone; candidates are timed as the timed region is (graph replay over the rotating sets)")
@@ -106,9 +106,13 @@ def main():
                      b_stride=(w.N * w.K, 1, w.K) if w.softmax else None)
     search = None
     if args.tune and tiles is None:
+        for i in range(max(args.warmup, 3000)):   # bring the clocks up before the first candidate is timed
+            step(i)
+        torch.cuda.synchronize()
+
         def measure(t):
             nonlocal tiles
-            tiles = (t.mb, t.rg, t.ns, t.nj)
+            tiles = (t.mb, t.rg, t.ns, t.nj, t.tl)
             reps = max(2 * n_sets, min(200, args.steps))
             for i in range(3):
                 step(i)
@@ -125,9 +129,11 @@ def main():
             torch.cuda.synchronize()
             return e0.elapsed_time(e1) * 1e-3 / reps
         best, rep = mcf.search_tiles(prob, w.softmax, measure, seed=w.seed)
-        tiles = (best.mb, best.rg, best.ns, best.nj)
+        tiles = (best.mb, best.rg, best.ns, best.nj, best.tl)
         search = {"measured": rep.measured, "generations": rep.generations, "converged": bool(rep.converged),
-                  "best_us": rep.best_t_s * 1e6}
+                  "best_us": rep.best_t_s * 1e6,
+                  "log": [[e.generation, e.mb, e.rg, e.ns, e.nj, e.tl, round(e.t_est_s * 1e6, 3), round(e.t_meas_s * 1e6, 3)]
+                          for e in rep.entries()]}
     picked = mcf.pick_tiles(prob, w.softmax) if tiles is None else mcf.eval_tiles(prob, *tiles, softmax=w.softmax)
 
     # ---- warm-up (also sets kernel attributes before any capture) -------------------------
@@ -228,7 +234,7 @@ def main():
         "config": {"workload": f"{w.name}: batch={w.batch} M={w.M} K={w.K} N={w.N} L={w.L} {w.dtype}"
                                f"{' softmax' if w.softmax else ''}",
                    "tiles": {"mb": picked.mb, "rg": picked.rg, "ns": picked.ns, "nj": picked.nj, "tm": picked.tm,
-                             "tn": picked.tn, "stages": picked.stages},
+                             "tn": picked.tn, "tk": picked.tk, "tl": picked.tl, "stages": picked.stages},
                    "buffer_sets": n_sets, "launch": "eager" if args.eager else "hip_graph",
                    "tile_choice": "search" if search else ("given" if args.tiles else "model"), "search": search},
         "pct_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS, "tflops": tflops,

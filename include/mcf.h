@@ -71,7 +71,8 @@ typedef struct mcf_problem {
  * 32-column slices), waves = rg * ns.
  */
 typedef struct mcf_tiles {
-    int32_t tm, tn, tk, tl;   /* tile sizes T_M, T_N, T_K (= K, or 128 with a k loop), T_L (= L) */
+    int32_t tm, tn, tk, tl;   /* tile sizes T_M, T_N, T_K (= K, or 128 with a k loop), T_L (= L, */
+                              /* or a divisor of L: then block <-> (batch, m-tile, h-tile))      */
     int32_t mb, rg, ns, nj;   /* 32-row blocks per wave, wave row-groups, waves across n,        */
                               /* 32-column slices per wave and n-iteration (0 reads as 1)        */
     int32_t waves;            /* rg * ns, 64 lanes each                                          */
@@ -96,20 +97,26 @@ typedef struct mcf_tiles {
 int mcf_pick_tiles(const mcf_problem *problem, int softmax, mcf_tiles *out);
 
 /*
- * Evaluate the model for a caller-chosen (mb, rg, ns, nj) instead of picking: fills every other
- * field of *tiles.  MCF_EUNSUPPORTED if no built variant has that shape, MCF_EINVAL if it
+ * Evaluate the model for a caller-chosen (mb, rg, ns, nj) and T_L (tl; 0 reads as L) instead of
+ * picking: fills every other field of *tiles.  MCF_EUNSUPPORTED if no built variant has that shape, MCF_EINVAL if it
  * breaks a budget (LDS, registers) -- such a variant still runs unless it exceeds the LDS of
  * a compute unit.  Host only.
  */
 int mcf_eval_tiles(const mcf_problem *problem, int softmax, mcf_tiles *tiles);
 
-/* Number of built kernel variants and their (mb, rg, ns, nj) for the shape; host only.
- * Writes up to cap quadruples into shapes (4 ints each) and returns the total count. */
+/* Number of built kernel variants with T_L = L and their (mb, rg, ns, nj) for the shape; host
+ * only.  Writes up to cap quadruples into shapes (4 ints each) and returns the total count. */
 int mcf_list_variants(const mcf_problem *problem, int softmax, int32_t *shapes, int cap);
+
+/* The candidates mcf_pick_tiles and the search choose from, with their model terms: the feasible
+ * variants for T_L = L followed by those for every smaller T_L that divides L and has kernels
+ * (the h tiles are then blocks of their own: more parallel work, GEMM 1 repeated per h tile --
+ * Sec. III-A, deep expression m h n k).  Writes up to cap entries, returns the total.  Host only. */
+int mcf_list_candidates(const mcf_problem *problem, int softmax, mcf_tiles *out, int cap);
 
 /*
  * E = (A . B) . D   (Sec. III-A).  Device pointers; tiles_or_null == NULL means
- * mcf_pick_tiles() decides, otherwise only its mb, rg, ns, nj fields are read.  hip_stream is a
+ * mcf_pick_tiles() decides, otherwise only its mb, rg, ns, nj and tl (0 = L) fields are read.  hip_stream is a
  * hipStream_t (NULL = the default stream).  E must not overlap A, B or D.  batch, M or L of
  * zero is a no-op; N == 0 writes zeros.
  */
@@ -127,13 +134,14 @@ int mcf_softmax_gemm_chain(const mcf_problem *problem, float scale, const void *
 
 /*
  * Heuristic search over the built variants (Sec. IV-B, Alg. 1): a population of `population`
- * candidates drawn at random from the feasible variants (those mcf_pick_tiles would consider),
+ * candidates drawn at random (without repetition while unused ones remain) from the feasible
+ * variants (those mcf_list_candidates returns),
  * ranked by the model; the `top_n` distinct candidates with the smallest estimates are measured;
  * the search stops when the fastest of them is within `epsilon` (relative) of the best time seen
  * so far, otherwise the next population is drawn from the current one with probability
  * proportional to 1 / estimate and each drawn member gets the tile choice of one loop (m: the
- * pair mb, rg; n: the pair ns, nj) replaced by that of a random feasible variant that differs in
- * that loop only.  A candidate is measured at most once.  Random numbers are SplitMix64 of
+ * pair mb, rg; n: the pair ns, nj; h: T_L) replaced by that of a random feasible variant that
+ * differs in that loop only.  A candidate is measured at most once.  Random numbers are SplitMix64 of
  * (seed + counter).  Zero fields of *params read as the defaults 32, 8, 16 and 0.02.
  */
 typedef struct mcf_search_params {
@@ -149,7 +157,7 @@ typedef struct mcf_search_params {
 typedef struct mcf_search_entry {
     int32_t mb, rg, ns, nj;  /* the candidate                                              */
     int32_t generation;      /* generation (from 0) in which it was measured               */
-    int32_t reserved;
+    int32_t tl;              /* its T_L                                                    */
     double t_est_s;          /* its model estimate, eq. (2)                                */
     double t_meas_s;         /* what the measurement returned                              */
 } mcf_search_entry;
@@ -179,7 +187,8 @@ int mcf_search_tiles(const mcf_problem *problem, int softmax, const mcf_search_p
  * Alg. 1 measured on the device: every measured candidate runs 3 + `launches` times on
  * hip_stream over the caller's buffers (same argument rules as the two chain calls; softmax != 0
  * selects mcf_softmax_gemm_chain with `scale`), timed with HIP events around the last
- * `launches` (<= 0 reads as 20).  E is overwritten.  Synchronises hip_stream; creates and
+ * `launches` (<= 0 reads as 20), after up to 50 ms of untimed launches of the model's choice
+ * that bring the clocks up.  E is overwritten.  Synchronises hip_stream; creates and
  * destroys two HIP events, allocates no device memory.  Operands that fit the caches stay
  * resident between launches, so the times are warm-cache times.
  */

@@ -19,6 +19,9 @@ Steps, as in Alg. 1:
                     and in each change the tile size of one randomly chosen loop
 
 Readings taken where the listing is ambiguous:
+  * "randomly select N candidates": without repetition while the space has unused candidates (a
+    random permutation of the space, cut to N or topped up to N with further random draws), so
+    that a space no larger than N is covered by the first population.
   * "Topk(..., reverse=True)" after an ascending sort: the n members with the SMALLEST
     estimates (the text: "isolate the top n candidates for detailed measurement").
   * A population holds duplicates; the n measured members are the first n DISTINCT candidates
@@ -77,7 +80,15 @@ def heuristic_search(space, estimates, measure, N, n, epsilon, seed, max_generat
     assert len(space) == len(estimates) and len(space) > 0
     rng = rng if rng is not None else Uniforms(seed)
     n_loops = len(space[0])
-    population = [rng.below(len(space)) for _ in range(N)]            # generateCandidates
+    perm = list(range(len(space)))                                     # generateCandidates
+    population = []
+    for i in range(N):
+        if i < len(space):                      # without repetition while unused candidates remain
+            j = i + rng.below(len(space) - i)
+            perm[i], perm[j] = perm[j], perm[i]
+            population.append(perm[i])
+        else:
+            population.append(rng.below(len(space)))
     best_t, best_cand = 1e9, None
     measured, log = {}, []
     generation, converged = 0, False

@@ -3,6 +3,6 @@ over the C ABI of libmcf.so.  Every step of the path runs in the HIP kernels; th
 only marshals arguments.  Importing works without the built library, calling does not."""
 from .binding import (  # noqa: F401
     McfError, Problem, Tiles, gemm_chain, softmax_gemm_chain, pick_tiles, eval_tiles,
-    list_variants, library_path, load_library, status_string, search_tiles, tune_tiles, SearchParams,
+    list_variants, list_candidates, library_path, load_library, status_string, search_tiles, tune_tiles, SearchParams,
     SearchReport,
 )

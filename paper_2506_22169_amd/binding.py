@@ -53,7 +53,7 @@ class SearchParams(ctypes.Structure):
 class SearchEntry(ctypes.Structure):
     """struct mcf_search_entry"""
     _fields_ = [("mb", ctypes.c_int32), ("rg", ctypes.c_int32), ("ns", ctypes.c_int32), ("nj", ctypes.c_int32),
-                ("generation", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("generation", ctypes.c_int32), ("tl", ctypes.c_int32),
                 ("t_est_s", ctypes.c_double), ("t_meas_s", ctypes.c_double)]
 
 
@@ -89,13 +89,14 @@ def load_library():
     lib.mcf_pick_tiles.argtypes = [PP, ctypes.c_int, TP]
     lib.mcf_eval_tiles.argtypes = [PP, ctypes.c_int, TP]
     lib.mcf_list_variants.argtypes = [PP, ctypes.c_int, ctypes.POINTER(ctypes.c_int32), ctypes.c_int]
+    lib.mcf_list_candidates.argtypes = [PP, ctypes.c_int, TP, ctypes.c_int]
     SP, RP = ctypes.POINTER(SearchParams), ctypes.POINTER(SearchReport)
     lib.mcf_search_tiles.argtypes = [PP, ctypes.c_int, SP, MEASURE_FN, vp, TP, RP]
     lib.mcf_tune_tiles.argtypes = [PP, ctypes.c_int, ctypes.c_float, vp, vp, vp, vp, SP, ctypes.c_int, vp, TP, RP]
     lib.mcf_gemm_chain.argtypes = [PP, vp, vp, vp, vp, TP, vp]
     lib.mcf_softmax_gemm_chain.argtypes = [PP, ctypes.c_float, vp, vp, vp, vp, TP, vp]
     for f in (lib.mcf_pick_tiles, lib.mcf_eval_tiles, lib.mcf_list_variants, lib.mcf_gemm_chain,
-              lib.mcf_softmax_gemm_chain, lib.mcf_search_tiles, lib.mcf_tune_tiles):
+              lib.mcf_softmax_gemm_chain, lib.mcf_search_tiles, lib.mcf_tune_tiles, lib.mcf_list_candidates):
         f.restype = ctypes.c_int
     lib.mcf_status_string.argtypes = [ctypes.c_int]
     lib.mcf_status_string.restype = ctypes.c_char_p
@@ -179,9 +180,9 @@ def _tiles_arg(tiles):
         return None
     if isinstance(tiles, Tiles):
         return ctypes.byref(tiles)
-    mb, rg, ns, nj = tiles
     t = Tiles()
-    t.mb, t.rg, t.ns, t.nj = mb, rg, ns, nj
+    t.mb, t.rg, t.ns, t.nj = tiles[:4]
+    t.tl = tiles[4] if len(tiles) > 4 else 0    # (mb, rg, ns, nj[, tl]); tl = 0 means T_L = L
     return ctypes.byref(t)
 
 
@@ -219,15 +220,25 @@ def pick_tiles(problem, softmax=False):
     return t
 
 
-def eval_tiles(problem, mb, rg, ns, nj=1, softmax=False):
-    """mcf_eval_tiles: model terms of a caller-chosen wave arrangement; host only."""
+def eval_tiles(problem, mb, rg, ns, nj=1, tl=0, softmax=False):
+    """mcf_eval_tiles: model terms of a caller-chosen wave arrangement (and T_L; 0 = L); host only."""
     t = Tiles()
-    t.mb, t.rg, t.ns, t.nj = mb, rg, ns, nj
+    t.mb, t.rg, t.ns, t.nj, t.tl = mb, rg, ns, nj, tl
     st = load_library().mcf_eval_tiles(ctypes.byref(problem), int(bool(softmax)), ctypes.byref(t))
     if st not in (MCF_OK, 1):     # MCF_EINVAL = evaluated, but over a budget: terms are filled in
         _check(st)
     t.feasible = (st == MCF_OK)
     return t
+
+
+def list_candidates(problem, softmax=False):
+    """mcf_list_candidates: the feasible candidates (Tiles with model terms) the picker and the
+    search choose from, T_L = L first, then every smaller T_L that has kernels."""
+    lib = load_library()
+    n = lib.mcf_list_candidates(ctypes.byref(problem), int(bool(softmax)), None, 0)
+    buf = (Tiles * max(n, 1))()
+    lib.mcf_list_candidates(ctypes.byref(problem), int(bool(softmax)), buf, n)
+    return [buf[i] for i in range(n)]
 
 
 def list_variants(problem, softmax=False):

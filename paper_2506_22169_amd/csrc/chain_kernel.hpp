@@ -162,7 +162,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     const unsigned lds0 = (unsigned)(size_t)smem;
 
     // kernel arguments -> scalar registers, once
-    const int M = p.M, N = p.N, m_tiles = p.m_tiles, n_blocks = p.n_blocks, a_mode = p.a_mode;
+    const int M = p.M, N = p.N, m_tiles = p.m_tiles, h_tiles = p.h_tiles, n_blocks = p.n_blocks, a_mode = p.a_mode;
     const int sa_r = (int)p.sa_r, sb_r = (int)p.sb_r, sd_r = (int)p.sd_r;
     const int64_t se_r = p.se_r;
     const float c1 = p.c1;
@@ -183,14 +183,18 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         const int x = hw & 7, q = n_blocks >> 3, rem = n_blocks & 7;
         logical = x * q + (x < rem ? x : rem) + (hw >> 3);
     }
-    const int batch = logical / m_tiles;
-    const int mt = logical - batch * m_tiles;
+    // With T_L < L (h_tiles > 1) the LD columns [ht * LD, ht * LD + LD) of D and E are a block
+    // of their own; the h tiles of one (batch, m-tile) are neighbours, so they share A and B in L2.
+    const int bm = h_tiles == 1 ? logical : logical / h_tiles;
+    const int ht = logical - bm * h_tiles;
+    const int batch = bm / m_tiles;
+    const int mt = bm - batch * m_tiles;
     const int mrow0 = mt * TM; // first row of the block
 
     const T *Ag = (const T *)p.A + batch * p.sa_b + (int64_t)mrow0 * sa_r;
     const T *Bg = (const T *)p.B + batch * p.sb_b;
-    const T *Dg = (const T *)p.D + batch * p.sd_b;
-    T *Eg = (T *)p.E + batch * p.se_b;
+    const T *Dg = (const T *)p.D + batch * p.sd_b + ht * LD;
+    T *Eg = (T *)p.E + batch * p.se_b + ht * LD;
 
     MCF_TRACE_POINT(0);
     // ---- per-lane byte offsets of the B / D pieces this wave loads for every n-tile ----------

@@ -96,14 +96,17 @@ static int run(const mcf_problem *p, int softmax, float scale, const void *A, co
         st = mcf_pick_tiles(p, softmax, &chosen);
         if (st != MCF_OK) return st;
     }
-    const Variant *v = find_variant(p->in_dtype, p->K, p->L, softmax, lay.b_kcontig, chosen.mb, chosen.rg, chosen.ns, chosen.nj > 0 ? chosen.nj : 1);
+    const int64_t tl = chosen.tl > 0 ? chosen.tl : p->L;
+    if (p->L % tl != 0) return MCF_EINVAL;
+    const Variant *v = find_variant(p->in_dtype, p->K, tl, softmax, lay.b_kcontig, chosen.mb, chosen.rg, chosen.ns, chosen.nj > 0 ? chosen.nj : 1);
     if (!v) return tiles ? MCF_EINVAL : MCF_EUNSUPPORTED;
     if (lds_bytes_for(v) > kLdsBytesPerBlock)
         return MCF_EINVAL; // more LDS than a compute unit has
 
     const int64_t tm = 32ll * v->mb * v->rg;
     const int64_t m_tiles = (p->M + tm - 1) / tm;
-    if (p->batch * m_tiles >= (1ll << 31)) return MCF_EUNSUPPORTED;
+    const int64_t h_tiles = p->L / tl;
+    if (p->batch * m_tiles * h_tiles >= (1ll << 31)) return MCF_EUNSUPPORTED;
 
     KParams k;
     memset(&k, 0, sizeof(k));
@@ -114,7 +117,8 @@ static int run(const mcf_problem *p, int softmax, float scale, const void *A, co
     k.se_b = lay.se[0]; k.se_r = lay.se[1];
     k.M = (int32_t)p->M; k.N = (int32_t)p->N;
     k.m_tiles = (int32_t)m_tiles;
-    k.n_blocks = (int32_t)(p->batch * m_tiles);
+    k.h_tiles = (int32_t)h_tiles;
+    k.n_blocks = (int32_t)(p->batch * m_tiles * h_tiles);
     k.c1 = 1.0f; k.a_mode = 0;
     k.k_chunks = (int32_t)(p->K / v->K);
     if (softmax) {

@@ -29,7 +29,8 @@ struct KParams {
     int64_t se_b, se_r; // E: batch / row stride
     int32_t M, N;
     int32_t m_tiles;    // ceil(M / T_M)
-    int32_t n_blocks;   // batch * m_tiles
+    int32_t h_tiles;    // L / T_L: column tiles of E, each a block of its own (1 when T_L = L)
+    int32_t n_blocks;   // batch * m_tiles * h_tiles
     float c1;           // |scale| * log2(e) (softmax only)
     int32_t a_mode;     // 0: A as is, 1: -A (negative scale), 2: A := 0 (scale == 0)
     int32_t k_chunks;   // kernels with a k loop: K / T_K (otherwise unused)

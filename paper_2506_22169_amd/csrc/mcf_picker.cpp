@@ -75,7 +75,7 @@ static void eval_model(const mcf_problem *p, int softmax, const Variant *v, mcf_
     const int mb = v->mb, rg = v->rg, ns = v->ns, nj = v->nj;
     memset(t, 0, sizeof(*t));
     t->mb = mb; t->rg = rg; t->ns = ns; t->nj = nj;
-    t->tm = 32 * mb * rg; t->tn = 32 * ns * nj; t->tk = v->K; t->tl = (int32_t)p->L;
+    t->tm = 32 * mb * rg; t->tn = 32 * ns * nj; t->tk = v->K; t->tl = v->L;
     t->waves = rg * ns;
     t->stages = stages_for(v);
     t->lds_bytes = lds_bytes_for(v);
@@ -84,18 +84,21 @@ static void eval_model(const mcf_problem *p, int softmax, const Variant *v, mcf_
     t->scratch_bytes = v->scratch_bytes;
     const int64_t es = 2; // bytes per element, fp16 / bf16
     const int64_t m = (p->M + t->tm - 1) / t->tm, n = (p->N + t->tn - 1) / t->tn;
-    t->blocks = p->batch * m;
+    // T_L < L: h is a second block dimension (deep expression m h n k): every h tile repeats
+    // L_A, L_B and C_C of its (batch, m-tile)
+    const int64_t h = p->L / t->tl;
+    t->blocks = p->batch * m * h;
     // N_block of eq. (5) counted in waves, against the machine's wave slots (below)
     const int64_t units = t->blocks * (t->waves < kWaveUnitsPerBlock ? t->waves : kWaveUnitsPerBlock);
     t->compulsory_bytes = es * p->batch * (p->M * p->K + p->K * p->N + p->N * p->L + p->M * p->L);
     // with a live k loop (T_K < K) inside n, L_A is no longer hoisted out of n: trips m * n * k
     const int64_t k = (p->K + t->tk - 1) / t->tk;
-    const int64_t la = (int64_t)t->tm * t->tk * es * p->batch * m * (k > 1 ? n * k : 1);
-    const int64_t lb = (int64_t)t->tk * t->tn * es * p->batch * m * n * k;
-    const int64_t ld = (int64_t)t->tn * p->L * es * p->batch * m * n;
-    const int64_t se = (int64_t)t->tm * p->L * es * p->batch * m;
+    const int64_t la = (int64_t)t->tm * t->tk * es * p->batch * m * h * (k > 1 ? n * k : 1);
+    const int64_t lb = (int64_t)t->tk * t->tn * es * p->batch * m * h * n * k;
+    const int64_t ld = (int64_t)t->tn * t->tl * es * p->batch * m * h * n;
+    const int64_t se = (int64_t)t->tm * t->tl * es * p->batch * m * h;
     t->model_bytes = la + lb + ld + se;
-    t->flops = (2 * (int64_t)t->tm * t->tn * t->tk * k + 2 * (int64_t)t->tm * t->tn * p->L) * p->batch * m * n;
+    t->flops = (2 * (int64_t)t->tm * t->tn * t->tk * k + 2 * (int64_t)t->tm * t->tn * t->tl) * p->batch * m * h * n;
     const int64_t reread = t->model_bytes > t->compulsory_bytes ? t->model_bytes - t->compulsory_bytes : 0;
     t->t_mem_s = (double)t->compulsory_bytes / kHbmBytesPerSec + (double)reread / kL2BytesPerSec;
     t->t_comp_s = (double)t->flops / kMfmaFlopsPerSec;
@@ -113,6 +116,7 @@ static bool feasible(const mcf_tiles &t) {
 // to combine), then more column slices per wave, then fewer rows per wave.
 static bool better(const mcf_tiles &a, const mcf_tiles &b) {
     if (a.t_est_s != b.t_est_s) return a.t_est_s < b.t_est_s;
+    if (a.tl != b.tl) return a.tl > b.tl;
     if (a.waves != b.waves) return a.waves > b.waves;
     const bool a2 = 2 * a.lds_bytes <= kLdsBytesPerBlock, b2 = 2 * b.lds_bytes <= kLdsBytesPerBlock;
     if (a2 != b2) return a2;
@@ -155,15 +159,18 @@ extern "C" int mcf_eval_tiles(const mcf_problem *p, int softmax, mcf_tiles *t) {
     int st = check_problem(p, &lay);
     if (st != MCF_OK) return st;
     const int mb = t->mb, rg = t->rg, ns = t->ns, nj = t->nj > 0 ? t->nj : 1;
-    const Variant *v = find_variant(p->in_dtype, p->K, p->L, softmax != 0, lay.b_kcontig, mb, rg, ns, nj);
+    const int64_t tl = t->tl > 0 ? t->tl : p->L;
+    if (p->L % tl != 0) return MCF_EUNSUPPORTED;
+    const Variant *v = find_variant(p->in_dtype, p->K, tl, softmax != 0, lay.b_kcontig, mb, rg, ns, nj);
     if (!v) return MCF_EUNSUPPORTED;
     eval_model(p, softmax != 0, v, t);
     return feasible(*t) ? MCF_OK : MCF_EINVAL;
 }
 
-// The candidates the picker and the search choose from, in registry order: feasible variants
-// that satisfy Rule 3; if Rule 3 leaves nothing (e.g. M smaller than every tile) it is dropped
-// so that a feasible variant is always found when one covers the shape.
+// The candidates the picker and the search choose from: for T_L = L and then for every smaller
+// T_L that divides L and has kernels, in registry order, the feasible variants that satisfy
+// Rule 3; if Rule 3 leaves nothing (e.g. M smaller than every tile) it is dropped so that a
+// feasible variant is always found when one covers the shape.
 int mcf::feasible_candidates(const mcf_problem *p, int softmax, std::vector<mcf_tiles> *out) {
     Layout lay;
     int st = check_problem(p, &lay);
@@ -171,21 +178,37 @@ int mcf::feasible_candidates(const mcf_problem *p, int softmax, std::vector<mcf_
     int n = 0, tk = 0, ksplit = 0;
     if (!resolve_group(p->in_dtype, p->K, p->L, &tk, &ksplit)) return MCF_EUNSUPPORTED;
     const Variant *v = variants(&n);
+    std::vector<int> tls; // T_L options, the full L first, then descending
+    tls.push_back((int)p->L);
+    for (int tl = (int)p->L / 2; tl >= 32; --tl) {
+        int tk2 = 0, ks2 = 0;
+        if (p->L % tl == 0 && resolve_group(p->in_dtype, p->K, tl, &tk2, &ks2)) tls.push_back(tl);
+    }
     for (int pass = 0; pass < 2; ++pass) {
         out->clear();
-        for (int i = 0; i < n; ++i) {
-            if (v[i].dtype != p->in_dtype || v[i].K != tk || v[i].ksplit != ksplit || v[i].L != p->L ||
-                v[i].softmax != (softmax != 0) || v[i].b_kcontig != lay.b_kcontig)
-                continue;
-            mcf_tiles t;
-            eval_model(p, softmax != 0, &v[i], &t);
-            if (!feasible(t)) continue;
-            if (pass == 0 && p->M > 0 && p->N > 0 && !(padding_ok(p->M, t.tm) && padding_ok(p->N, t.tn))) continue;
-            out->push_back(t);
+        for (int tl : tls) {
+            resolve_group(p->in_dtype, p->K, tl, &tk, &ksplit);
+            for (int i = 0; i < n; ++i) {
+                if (v[i].dtype != p->in_dtype || v[i].K != tk || v[i].ksplit != ksplit || v[i].L != tl ||
+                    v[i].softmax != (softmax != 0) || v[i].b_kcontig != lay.b_kcontig)
+                    continue;
+                mcf_tiles t;
+                eval_model(p, softmax != 0, &v[i], &t);
+                if (!feasible(t)) continue;
+                if (pass == 0 && p->M > 0 && p->N > 0 && !(padding_ok(p->M, t.tm) && padding_ok(p->N, t.tn))) continue;
+                out->push_back(t);
+            }
         }
         if (!out->empty()) return MCF_OK;
     }
     return MCF_EUNSUPPORTED;
+}
+
+extern "C" int mcf_list_candidates(const mcf_problem *p, int softmax, mcf_tiles *out, int cap) {
+    std::vector<mcf_tiles> cands;
+    if (feasible_candidates(p, softmax, &cands) != MCF_OK) return 0;
+    for (int i = 0; i < (int)cands.size() && out && i < cap; ++i) out[i] = cands[i];
+    return (int)cands.size();
 }
 
 extern "C" int mcf_pick_tiles(const mcf_problem *p, int softmax, mcf_tiles *out) {

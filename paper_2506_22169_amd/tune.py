@@ -74,9 +74,9 @@ def main(argv=None):
           f"{rep.space} feasible variants, {rep.measured} measured in {rep.generations} generations, "
           f"{'converged' if rep.converged else 'generation bound reached'}")
     for e in rep.entries():
-        print(f"  gen {e.generation}  ({e.mb},{e.rg},{e.ns},{e.nj})  model {e.t_est_s * 1e6:9.2f} us  measured {e.t_meas_s * 1e6:9.2f} us")
-    print(f"search result ({best.mb},{best.rg},{best.ns},{best.nj}) at {rep.best_t_s * 1e6:.2f} us; "
-          f"closed-form pick ({pick.mb},{pick.rg},{pick.ns},{pick.nj})")
+        print(f"  gen {e.generation}  ({e.mb},{e.rg},{e.ns},{e.nj}) T_L={e.tl}  model {e.t_est_s * 1e6:9.2f} us  measured {e.t_meas_s * 1e6:9.2f} us")
+    print(f"search result ({best.mb},{best.rg},{best.ns},{best.nj}) T_L={best.tl} at {rep.best_t_s * 1e6:.2f} us; "
+          f"closed-form pick ({pick.mb},{pick.rg},{pick.ns},{pick.nj}) T_L={pick.tl}")
     if a.all:
         def run(t):
             if a.softmax:
@@ -84,10 +84,8 @@ def main(argv=None):
             else:
                 mcf.gemm_chain(A, B, D, out=E, tiles=t)
         est, meas = [], []
-        for v in mcf.list_variants(prob, a.softmax):
-            t = mcf.eval_tiles(prob, *v, softmax=a.softmax)
-            if not t.feasible:
-                continue
+        for t in mcf.list_candidates(prob, a.softmax):
+            v = (t.mb, t.rg, t.ns, t.nj, t.tl)
             s = time_variant(run, v, a.launches)
             est.append(t.t_est_s)
             meas.append(s)

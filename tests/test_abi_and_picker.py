@@ -67,48 +67,56 @@ _BUILT_PAPER_SHAPES = list(mi.PAPER_SHAPES)
 
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"] + _BUILT_PAPER_SHAPES)
 def test_picker_terms_match_the_paper_model(name):
-    """Every model term of every built variant equals eq. (2)-(5) evaluated by the oracle model
-    for the tiling expression mhnk with T_K = K, T_L = L, and the picked variant is the
-    feasible one with the smallest estimate."""
+    """Every model term of every built variant, for T_L = L and for every smaller T_L that has
+    kernels, equals eq. (2)-(5) evaluated by the oracle model for the tiling expression mhnk,
+    and the picked variant is the feasible one with the smallest estimate."""
     w = mi.WORKLOADS[name] if name in mi.WORKLOADS else mi.PAPER_SHAPES[name]
     prob = _c_problem(w)
     shapes = mcf.list_variants(prob, w.softmax)
     assert len(shapes) >= (8 if w.K * w.L <= 128 * 128 else 3)
     dims = {"m": w.M, "n": w.N, "k": w.K, "h": w.L}
-    best = None
-    for (mb, rg, ns, nj) in shapes:
-        t = mcf.eval_tiles(prob, mb, rg, ns, nj, softmax=w.softmax)
-        assert (t.tm, t.tn, t.tl, t.waves) == (32 * mb * rg, 32 * ns * nj, w.L, rg * ns)
-        assert t.tk == (w.K if w.K <= 256 else 128)
-        pitch = lambda x: 1 << (x - 1).bit_length()   # LDS rows are laid out with a power-of-two pitch
-        tiles = {"m": t.tm, "n": t.tn, "k": t.tk, "h": w.L}
-        units_per_block = (t.waves + 3) // 4
-        # eq. (5) in waves: N_block = blocks x min(waves, 6), N_SM = 256 compute units x 6
-        r = pm.estimate("mhnk", dims, tiles, w.batch, 2, W=W_HBM, P=P_MFMA, n_units=CUS * WAVE_CAP / min(t.waves, WAVE_CAP),
-                        W_reread=W_L2)
-        assert t.blocks == r["n_block"]
-        assert t.compulsory_bytes == r["compulsory_bytes"] == w.compulsory_bytes
-        assert t.model_bytes == r["model_bytes"]
-        assert t.flops == r["flops"]
-        assert t.t_mem_s == pytest.approx(r["t_mem"], rel=1e-12)
-        assert t.t_comp_s == pytest.approx(r["t_comp"], rel=1e-12)
-        assert t.alpha == pytest.approx(r["alpha"], rel=1e-12)
-        assert t.t_est_s == pytest.approx(r["t_estm"], rel=1e-12)
-        # eq. (1), split: LDS holds `stages` copies of the B and D tiles (plus the A tile in the last slot)
-        padded = dict(tiles, k=pitch(t.tk), h=pitch(w.L))
-        bd = pm.shm_estm(padded, "BD") * 2
-        a = pm.tile_elems("A", padded) * 2
-        assert 2 <= t.stages <= 4
-        if t.tk < w.K:   # k loop: a ring slot holds the A + B chunk of a k step or the D tile
-            ab = (pm.tile_elems("A", tiles) + pm.tile_elems("B", tiles)) * 2
-            assert t.lds_bytes >= t.stages * max(ab, pm.tile_elems("D", tiles) * 2)
-        else:
-            assert t.lds_bytes >= (t.stages - 1) * bd + max(bd, a)
-        ok = (t.lds_bytes <= LDS_MAX and t.scratch_bytes == 0 and t.vgpr_est <= 512 // units_per_block
-              and pm.padding_ok(w.M, t.tm) and pm.padding_ok(w.N, t.tn))
-        assert ok == (t.feasible and pm.padding_ok(w.M, t.tm) and pm.padding_ok(w.N, t.tn))
-        if ok and (best is None or t.t_est_s < best.t_est_s * (1 - 1e-12)):
-            best = t
+    pitch = lambda x: 1 << (x - 1).bit_length()   # LDS rows are laid out with a power-of-two pitch
+    tl_options = [w.L] + [tl for tl in (256, 128, 64, 32) if tl < w.L and w.L % tl == 0]
+    best, n_ok = None, 0
+    for tl in tl_options:
+        # the arrangements built for (K, T_L): those of a problem whose L is T_L
+        narrow = make_problem(w.batch, w.M, w.K, w.N, tl, w.dtype, b_stride=(w.N * w.K, 1, w.K) if w.softmax else None)
+        for (mb, rg, ns, nj) in mcf.list_variants(narrow, w.softmax):
+            t = mcf.eval_tiles(prob, mb, rg, ns, nj, tl=tl, softmax=w.softmax)
+            assert (t.tm, t.tn, t.tl, t.waves) == (32 * mb * rg, 32 * ns * nj, tl, rg * ns)
+            assert t.tk == (w.K if w.K <= 256 and (w.K, tl) != (256, 128) and (w.K, tl) != (256, 64) else 128)
+            tiles = {"m": t.tm, "n": t.tn, "k": t.tk, "h": tl}
+            units_per_block = (t.waves + 3) // 4
+            # eq. (5) in waves: N_block = blocks x min(waves, 6), N_SM = 256 compute units x 6
+            r = pm.estimate("mhnk", dims, tiles, w.batch, 2, W=W_HBM, P=P_MFMA,
+                            n_units=CUS * WAVE_CAP / min(t.waves, WAVE_CAP), W_reread=W_L2)
+            assert t.blocks == r["n_block"]
+            assert t.compulsory_bytes == r["compulsory_bytes"] == w.compulsory_bytes
+            assert t.model_bytes == r["model_bytes"]
+            assert t.flops == r["flops"]
+            assert t.t_mem_s == pytest.approx(r["t_mem"], rel=1e-12)
+            assert t.t_comp_s == pytest.approx(r["t_comp"], rel=1e-12)
+            assert t.alpha == pytest.approx(r["alpha"], rel=1e-12)
+            assert t.t_est_s == pytest.approx(r["t_estm"], rel=1e-12)
+            # eq. (1), split: LDS holds `stages` copies of the B and D tiles (plus the A tile in the last slot)
+            padded = dict(tiles, k=pitch(t.tk), h=pitch(tl))
+            bd = pm.shm_estm(padded, "BD") * 2
+            a = pm.tile_elems("A", padded) * 2
+            assert 2 <= t.stages <= 4
+            if t.tk < w.K:   # k loop: a ring slot holds the A + B chunk of a k step or the D tile
+                ab = (pm.tile_elems("A", tiles) + pm.tile_elems("B", tiles)) * 2
+                assert t.lds_bytes >= t.stages * max(ab, pm.tile_elems("D", tiles) * 2)
+            else:
+                assert t.lds_bytes >= (t.stages - 1) * bd + max(bd, a)
+            ok = (t.lds_bytes <= LDS_MAX and t.scratch_bytes == 0 and t.vgpr_est <= 512 // units_per_block
+                  and pm.padding_ok(w.M, t.tm) and pm.padding_ok(w.N, t.tn))
+            assert ok == (t.feasible and pm.padding_ok(w.M, t.tm) and pm.padding_ok(w.N, t.tn))
+            n_ok += ok
+            if ok and (best is None or t.t_est_s < best.t_est_s * (1 - 1e-12)):
+                best = t
+    cands = mcf.list_candidates(prob, w.softmax)
+    assert len(cands) == n_ok                      # the candidate list is exactly the feasible set
+    assert cands[0].tl == w.L and all(c.tl <= w.L and w.L % c.tl == 0 for c in cands)
     picked = mcf.pick_tiles(prob, w.softmax)
     assert best is not None
     assert picked.t_est_s == pytest.approx(best.t_est_s, rel=1e-12)
@@ -128,7 +136,7 @@ def test_shapes_without_kernels_are_refused():
     for name in ("G5", "G6"):
         w = mi.PAPER_SHAPES[name]
         assert lib.mcf_pick_tiles(ctypes.byref(_c_problem(w)), 0, ctypes.byref(t)) == 0
-        assert (t.tk, t.tl) == (128, 256) and t.tk < w.K
+        assert t.tk == 128 and t.tk < w.K and w.L % t.tl == 0
 
 
 def test_register_estimate_tracks_the_compiler():

@@ -38,6 +38,24 @@ def test_every_variant_small_ragged(KL, dtype, softmax):
     print(f"worst max|err|/max|oracle| = {worst:.3e}", flush=True)
 
 
+@pytest.mark.parametrize("softmax", [False, True])
+@pytest.mark.parametrize("KL", [(64, 256), (128, 128), (384, 128), (256, 256)])
+def test_h_tiles_every_candidate(KL, softmax):
+    """T_L < L: the column tiles of E are blocks of their own (grid over batch, m-tile, h-tile).
+    Every feasible candidate with T_L < L, on a shape with ragged m and n tails."""
+    K, L = KL
+    M, N = 333, (200 if not softmax else 203)
+    w = mi.make_problem(2, M, K, N, L, "f16", softmax, "normal" if softmax else "uniform", seed=5000 + K + L)
+    prob = c_problem(2, M, K, N, L, "f16", b_stride=(N * K, 1, K) if softmax else None)
+    cands = [(t.mb, t.rg, t.ns, t.nj, t.tl) for t in mcf.list_candidates(prob, softmax) if t.tl < L]
+    assert len(cands) >= 6 and len({c[4] for c in cands}) >= (2 if L == 256 else 1)
+    worst = 0.0
+    for tiles in cands:
+        print(f"case K={K} L={L} softmax={softmax} tiles={tiles}", flush=True)
+        worst = max(worst, check_full(w, tiles))
+    print(f"worst max|err|/max|oracle| = {worst:.3e}", flush=True)
+
+
 @pytest.mark.parametrize("layout", ["kn", "nk"])
 @pytest.mark.parametrize("softmax", [False, True])
 def test_both_b_layouts(softmax, layout):

@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 
 @pytest.mark.parametrize("softmax", [False, True])
 def test_tune_returns_a_measured_feasible_variant(softmax):
-    w = mi.make_problem(8, 512, 64, 384, 64, "f16", softmax, "normal" if softmax else "uniform", seed=4242)
+    w = mi.make_problem(8, 512, 64, 384, 128, "f16", softmax, "normal" if softmax else "uniform", seed=4242)
     x = mi.make_inputs(w)
     A, B, D = device_inputs(w, x)
     E = torch.empty((w.batch, w.M, w.L), dtype=A.dtype, device="cuda")
@@ -24,17 +24,17 @@ def test_tune_returns_a_measured_feasible_variant(softmax):
     best, rep = mcf.tune_tiles(A, B, D, scale=w.scale if softmax else None, out=E, launches=10, population=16,
                                top_n=4, seed=3)
     prob = mcf.binding._problem_from_tensors(A, B, D, E)
-    shapes = mcf.list_variants(prob, softmax)
+    shapes = [(t.mb, t.rg, t.ns, t.nj, t.tl) for t in mcf.list_candidates(prob, softmax)]
     entries = rep.entries()
     assert 1 <= rep.measured == len(entries) <= 4 * rep.generations
-    assert rep.space <= len(shapes)
-    seen = [(e.mb, e.rg, e.ns, e.nj) for e in entries]
+    assert rep.space == len(shapes)
+    seen = [(e.mb, e.rg, e.ns, e.nj, e.tl) for e in entries]
     assert len(set(seen)) == len(seen) and all(s in shapes for s in seen)
     for e in entries:
-        t = mcf.eval_tiles(prob, e.mb, e.rg, e.ns, e.nj, softmax=softmax)
+        t = mcf.eval_tiles(prob, e.mb, e.rg, e.ns, e.nj, tl=e.tl, softmax=softmax)
         assert t.feasible and t.t_est_s == e.t_est_s and 0 < e.t_meas_s < 1e-2
-    assert (best.mb, best.rg, best.ns, best.nj) in seen
-    assert rep.best_t_s == [e.t_meas_s for e in entries if (e.mb, e.rg, e.ns, e.nj) == (best.mb, best.rg, best.ns, best.nj)][0]
+    assert (best.mb, best.rg, best.ns, best.nj, best.tl) in seen
+    assert rep.best_t_s == [e.t_meas_s for e, s in zip(entries, seen) if s == (best.mb, best.rg, best.ns, best.nj, best.tl)][0]
     fastest = min(e.t_meas_s for e in entries)
     assert rep.best_t_s <= fastest * 1.02 + 1e-12 if rep.converged else rep.best_t_s == fastest
     # E holds the result of the last measured launch; run once more with the returned tiles

@@ -13,15 +13,11 @@ from paper_2506_22169_amd.binding import make_problem
 
 
 def _space(w):
-    """Feasible candidates in the library's order with the library's estimates (each estimate is
-    checked against the oracle model in test_abi_and_picker) under Rule 3."""
+    """Feasible candidates in the library's order with the library's estimates (each estimate and
+    the membership of the list are checked against the oracle model in test_abi_and_picker)."""
     prob = make_problem(w.batch, w.M, w.K, w.N, w.L, w.dtype, b_stride=(w.N * w.K, 1, w.K) if w.softmax else None)
-    shapes, tiles = [], []
-    for v in mcf.list_variants(prob, w.softmax):
-        t = mcf.eval_tiles(prob, *v, softmax=w.softmax)
-        if t.feasible and pm.padding_ok(w.M, t.tm) and pm.padding_ok(w.N, t.tn):
-            shapes.append(v)
-            tiles.append(t)
+    tiles = mcf.list_candidates(prob, w.softmax)
+    shapes = [(t.mb, t.rg, t.ns, t.nj, t.tl) for t in tiles]
     return prob, shapes, tiles
 
 
@@ -31,7 +27,7 @@ def _table(shapes, tiles, wobble_seed):
     return {v: t.t_est_s * (0.6 + 0.8 * rng.next()) for v, t in zip(shapes, tiles)}
 
 
-CASES = [(name, N, n, seed) for name in ("cfg2", "cfg3", "cfg5", "G3", "S8")
+CASES = [(name, N, n, seed) for name in ("cfg2", "cfg3", "cfg5", "G3", "G6", "S8")
          for (N, n, seed) in ((32, 8, 1), (6, 2, 7), (4, 1, 3), (12, 3, 11))]
 
 
@@ -41,23 +37,23 @@ def test_library_search_equals_oracle_search(name, N, n, seed):
     prob, shapes, tiles = _space(w)
     assert len(shapes) >= 3
     table = _table(shapes, tiles, 100 + seed)
-    space = [((mb, rg), (ns, nj)) for (mb, rg, ns, nj) in shapes]
+    space = [((mb, rg), (ns, nj), (tl,)) for (mb, rg, ns, nj, tl) in shapes]   # loops m, n, h
     est = [t.t_est_s for t in tiles]
     want = sr.heuristic_search(space, est, lambda c: table[shapes[c]], N=N, n=n, epsilon=0.02, seed=seed,
                                max_generations=16)
     calls = []
 
     def measure(t):
-        calls.append((t.mb, t.rg, t.ns, t.nj))
-        return table[(t.mb, t.rg, t.ns, t.nj)]
+        calls.append((t.mb, t.rg, t.ns, t.nj, t.tl))
+        return table[(t.mb, t.rg, t.ns, t.nj, t.tl)]
 
     best, rep = mcf.search_tiles(prob, w.softmax, measure, population=N, top_n=n, epsilon=0.02, seed=seed,
                                  max_generations=16)
     assert rep.space == len(shapes)
     assert calls == [shapes[c] for _, c, _, _ in want["log"]]
-    got_log = [(e.generation, (e.mb, e.rg, e.ns, e.nj), e.t_est_s, e.t_meas_s) for e in rep.entries()]
+    got_log = [(e.generation, (e.mb, e.rg, e.ns, e.nj, e.tl), e.t_est_s, e.t_meas_s) for e in rep.entries()]
     assert got_log == [(g, shapes[c], est[c], t) for g, c, _, t in want["log"]]
-    assert (best.mb, best.rg, best.ns, best.nj) == shapes[want["best"]]
+    assert (best.mb, best.rg, best.ns, best.nj, best.tl) == shapes[want["best"]]
     assert rep.best_t_s == want["best_t"]
     assert (rep.generations, bool(rep.converged)) == (want["generations"], want["converged"])
     assert best.t_est_s == est[want["best"]]
@@ -69,7 +65,7 @@ def test_defaults_and_errors():
     # zero parameters read as N = 32, n = 8, epsilon = 0.02, 16 generations
     a = mcf.search_tiles(prob, False, lambda t: t.t_est_s, seed=9)
     b = mcf.search_tiles(prob, False, lambda t: t.t_est_s, population=32, top_n=8, epsilon=0.02, seed=9, max_generations=16)
-    assert [(e.mb, e.rg, e.ns, e.nj) for e in a[1].entries()] == [(e.mb, e.rg, e.ns, e.nj) for e in b[1].entries()]
+    assert [(e.mb, e.rg, e.ns, e.nj, e.tl) for e in a[1].entries()] == [(e.mb, e.rg, e.ns, e.nj, e.tl) for e in b[1].entries()]
     assert a[1].measured <= 8 * a[1].generations
     # measurement == model: the result is the picker's estimate
     assert a[0].t_est_s == pytest.approx(mcf.pick_tiles(prob, False).t_est_s, rel=1e-12)
