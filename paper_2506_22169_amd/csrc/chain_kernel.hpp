@@ -853,7 +853,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             const u32x4 v = *(const lds_u32x4 *)(es + 16 * slot);
             if (EPAD && (ch >= 4 * HPW || 32 * h0 + 8 * ch >= LD)) continue;
             if (rbase + row < M && (!(MCF_ABLATE & 8) || v[0] == 0x12345u))
-                *(u32x4 *)(Eg + (int64_t)(rbase + row) * se_r + 32 * h0 + 8 * ch) = v;
+                __builtin_nontemporal_store(v, (u32x4 *)(Eg + (int64_t)(rbase + row) * se_r + 32 * h0 + 8 * ch));
         }
     }
     MCF_TRACE_POINT(7);
