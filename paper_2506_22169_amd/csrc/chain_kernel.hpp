@@ -118,6 +118,13 @@ static __device__ __forceinline__ void dma16(unsigned lds_addr, unsigned voff, c
                  : "s"(uniform(lds_addr)), "v"(voff), "s"(uniform(base))
                  : "memory", "m0");
 }
+// The same for data the kernel reads once (the A tile): streaming hint.
+static __device__ __forceinline__ void dma16_once(unsigned lds_addr, unsigned voff, const void *base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
+                 :
+                 : "s"(uniform(lds_addr)), "v"(voff), "s"(uniform(base))
+                 : "memory", "m0");
+}
 template <int N> static __device__ __forceinline__ void wait_vm() {
     static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -358,7 +365,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             ch ^= swz_b128(RBA, row);
             if (KPAD && ch >= KCH) ch = 0;             // padding of the row: any valid piece
             if (mrow0 + row >= M) row = M - 1 - mrow0; // rows past M: any valid row, never stored
-            dma16(dst0 + (jj - wave) * 1024, (unsigned)(row * sa_r * 2 + ch * 16), abase);
+            dma16_once(dst0 + (jj - wave) * 1024, (unsigned)(row * sa_r * 2 + ch * 16), abase);
         }
     }
     const int n_items = KSPLIT ? n_iters * (KC + 1) : n_iters; // ring items of the whole block
