@@ -148,6 +148,8 @@ def _problem_from_tensors(A, B, D, E):
         raise McfError(1, "A, B, D, E must share one dtype")
     if not (A.is_cuda and B.is_cuda and D.is_cuda and E.is_cuda):
         raise McfError(1, "A, B, D, E must be device tensors")
+    if not (A.device == B.device == D.device == E.device):
+        raise McfError(1, "A, B, D, E must live on one device")
     code = _dtype_code(A)
 
     def st(t):

@@ -871,11 +871,18 @@ template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTM
 int launch_chain(const KParams &p, void *stream) {
     constexpr int lds = total_lds_bytes(KD, LD, MB, RG, NS, NJ, ring_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX, KSPLIT), KSPLIT);
     auto kern = chain_kernel<T, KD, LD, MB, RG, NS, NJ, SOFTMAX, BKC, KSPLIT>;
-    static bool attr_done = false; // benign race: setting the attribute twice is harmless
-    if (lds > 64 * 1024 && !attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    // More than 64 KiB of dynamic LDS has to be allowed per function and device, once.  (A race
+    // between two threads sets the attribute twice, which is harmless.)
+    if (lds > 64 * 1024) {
+        static bool attr_done[64] = {};
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
         if (e != hipSuccess) return (int)e;
-        attr_done = true;
+        if (dev < 0 || dev >= 64 || !attr_done[dev]) {
+            e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+            if (e != hipSuccess) return (int)e;
+            if (dev >= 0 && dev < 64) attr_done[dev] = true;
+        }
     }
     hipLaunchKernelGGL(kern, dim3(p.n_blocks), dim3(64 * RG * NS), lds, (hipStream_t)stream, p);
     return (int)hipGetLastError();
