@@ -39,6 +39,8 @@ def _load():
         lib.mcf_oracle_chain_rows.restype = ctypes.c_int
         lib.mcf_oracle_intermediate_row.argtypes = common + [i64, i64, dp]
         lib.mcf_oracle_intermediate_row.restype = None
+        lib.mcf_oracle_chain3.argtypes = common + [i64, dp, ip, dp]
+        lib.mcf_oracle_chain3.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -101,3 +103,23 @@ def intermediate_row(A, B, D, b, i, softmax=False, scale=1.0):
                                         row.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
     del keep
     return row[:N]
+
+
+def chain3(A, B, D, F, softmax=False, scale=1.0):
+    """Three-GEMM chain G = (E) . F with E = chain(A, B, D): F[b,L,P] -> float64 [b,M,P]."""
+    (b, M, K, N, L), args, keep = _prep(A, B, D)
+    F = np.asarray(F)
+    if F.dtype != np.float64 or F.ndim != 3 or F.shape[0] != b or F.shape[1] != L:
+        raise ValueError(f"F{F.shape} does not continue D's [b,N,{L}]")
+    if any(s % 8 for s in F.strides) or any(s < 0 for s in F.strides):
+        raise ValueError("strides must be non-negative multiples of the element size")
+    if softmax and N == 0:
+        raise ValueError("softmax over an empty row is undefined")
+    P = F.shape[2]
+    sf = np.array([s // 8 for s in F.strides], dtype=np.int64)
+    G = np.zeros((b, M, P), dtype=np.float64)
+    dp, ip = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)
+    _load().mcf_oracle_chain3(*args, int(bool(softmax)), float(scale), P, F.ctypes.data_as(dp),
+                              sf.ctypes.data_as(ip), G.ctypes.data_as(dp))
+    del keep
+    return G

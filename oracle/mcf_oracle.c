@@ -155,3 +155,44 @@ void mcf_oracle_intermediate_row(int64_t batch, int64_t M, int64_t K, int64_t N,
     chain_row(&p, b, i, row, out);
     free(out);
 }
+
+/*
+ * Chain of three GEMMs (Sec. III-A: the analysis "extends to scenarios with more
+ * compute-intensive operators"): G[b,i,p] = sum_h E[b,i,h] * F[b,h,p] with E as above (the
+ * softmax, if any, sits between the first two GEMMs).  One row of E is materialised per (b,i)
+ * and nothing is rounded.  G packed [batch, M, P].  Returns the number of threads used.
+ */
+int mcf_oracle_chain3(int64_t batch, int64_t M, int64_t K, int64_t N, int64_t L,
+                      const double *A, const int64_t *sa, const double *B, const int64_t *sb,
+                      const double *D, const int64_t *sd, int softmax, double scale,
+                      int64_t P, const double *F, const int64_t *sf, double *G)
+{
+    chain_t p;
+    fill(&p, batch, M, K, N, L, A, sa, B, sb, D, sd, softmax, scale);
+    int threads = 1;
+    const int64_t rows = batch * M;
+#pragma omp parallel
+    {
+#ifdef _OPENMP
+#pragma omp single
+        threads = omp_get_num_threads();
+#endif
+        double *crow = (double *)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1));
+        double *erow = (double *)malloc(sizeof(double) * (size_t)(L > 0 ? L : 1));
+#pragma omp for schedule(static)
+        for (int64_t r = 0; r < rows; ++r) {
+            const int64_t b = r / M;
+            chain_row(&p, b, r % M, crow, erow);
+            const double *Fb = F + b * sf[0];
+            for (int64_t q = 0; q < P; ++q) {
+                double s = 0.0;
+                for (int64_t h = 0; h < L; ++h)
+                    s += erow[h] * Fb[h * sf[1] + q * sf[2]];
+                G[r * P + q] = s;
+            }
+        }
+        free(crow);
+        free(erow);
+    }
+    return threads;
+}

@@ -145,3 +145,37 @@ def test_shape_and_empty_handling():
         oracle.chain(A, np.zeros((1, 3, 0)), np.zeros((1, 0, 5)), softmax=True)
     with pytest.raises(ValueError):
         oracle.chain(A, np.zeros((1, 4, 4)), np.zeros((1, 4, 5)))
+
+
+def test_chain3_bruteforce_and_identities():
+    """Three-GEMM chain: flat triple sum on small integers (bit equality; distinct extents so that
+    a swapped index shows), F = identity gives the two-GEMM chain, right-to-left association,
+    and the softmax form against a library softmax and matmul."""
+    rng = np.random.default_rng(21)
+    b, M, K, N, L, P = 2, 3, 4, 5, 2, 6
+    A, B, D, F = _ints(rng, (b, M, K)), _ints(rng, (b, K, N)), _ints(rng, (b, N, L)), _ints(rng, (b, L, P))
+    G = oracle.chain3(A, B, D, F)
+    assert G.shape == (b, M, P)
+    for bb in range(b):
+        for i in range(M):
+            for q in range(P):
+                s = 0.0
+                for h in range(L):
+                    for n in range(N):
+                        for k in range(K):
+                            s += A[bb, i, k] * B[bb, k, n] * D[bb, n, h] * F[bb, h, q]
+                assert G[bb, i, q] == s
+    eye = np.broadcast_to(np.eye(L), (b, L, L)).copy()
+    assert np.array_equal(oracle.chain3(A, B, D, eye), oracle.chain(A, B, D))
+    assert not oracle.chain3(A, B, D, np.zeros((b, L, P))).any()
+    # A . (B . (D . F)) on random doubles
+    A, B, D, F = (rng.standard_normal(s) for s in ((b, M, K), (b, K, N), (b, N, L), (b, L, P)))
+    ref = A @ (B @ (D @ F))
+    assert np.max(np.abs(oracle.chain3(A, B, D, F) - ref)) <= 1e-12 * np.max(np.abs(ref))
+    # softmax between the first two GEMMs; a transposed (strided) F view
+    Ft = np.ascontiguousarray(F.transpose(0, 2, 1)).transpose(0, 2, 1)
+    ref = (scipy_softmax(0.3 * (A @ B), axis=-1) @ D) @ F
+    got = oracle.chain3(A, B, D, Ft, softmax=True, scale=0.3)
+    assert np.max(np.abs(got - ref)) <= 1e-12 * np.max(np.abs(ref))
+    with pytest.raises(ValueError):
+        oracle.chain3(A, B, D, np.zeros((b, L + 1, P)))
