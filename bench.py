@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--tune", action="store_true",
                     help="choose the tiles by the measured search (Alg. 1) before the warm-up instead of by the "
                          "model alone; candidates are timed as the timed region is (graph replay over the rotating sets)")
+    ap.add_argument("--chain3", action="store_true",
+                    help="append a third GEMM: G = E . F with F[b, L, L] (built for K = L in {64, 128}); bytes and "
+                         "flops of the extra operand and GEMM are added to the figures")
     ap.add_argument("--eager", action="store_true", help="time plain calls instead of a HIP graph replay")
     ap.add_argument("--warm", action="store_true", help="reuse one buffer set (cache-resident operands)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -81,7 +84,16 @@ def main():
         return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(tdt).cuda()
 
     A0, B0s, D0 = dev(x["a_bits"]), dev(x["b_bits"]), dev(x["d_bits"])
-    per_set = w.compulsory_bytes
+    per_set, flops = w.compulsory_bytes, w.flops
+    P = w.L
+    if args.chain3:                       # F[b, L, P] read once; G[b, M, P] replaces E[b, M, L] (P = L)
+        if args.tune:
+            print("bench.py: --chain3 takes the model's tiles or --tiles, not --tune", file=sys.stderr)
+            return 2
+        f_bits = mi.to_bits(mi.draw(w.seed, 4, (w.batch, w.L, P), w.dist), w.dtype)
+        F0 = dev(f_bits)
+        per_set += 2 * w.batch * w.L * P
+        flops += 2 * w.batch * w.M * w.L * P
     n_sets = 1 if args.warm else max(2, min(64, math.ceil(768 * 2**20 / per_set)))
     if per_set * n_sets > 8 * 2**30:
         n_sets = max(2, (8 * 2**30) // per_set)
@@ -93,11 +105,14 @@ def main():
         D = D0 if s == 0 else torch.roll(D0, sh, 0).contiguous()
         B = Bs.transpose(1, 2) if w.softmax else Bs
         E = torch.empty((w.batch, w.M, w.L), dtype=tdt, device="cuda")
-        sets.append((A, B, D, E))
+        F = None if not args.chain3 else (F0 if s == 0 else torch.roll(F0, sh, 0).contiguous())
+        sets.append((A, B, D, E, F))
 
     def step(i):
-        A, B, D, E = sets[i % n_sets]
-        if w.softmax:
+        A, B, D, E, F = sets[i % n_sets]
+        if args.chain3:
+            mcf.gemm_chain3(A, B, D, F, scale=w.scale if w.softmax else None, out=E, tiles=tiles)
+        elif w.softmax:
             mcf.softmax_gemm_chain(A, B, D, w.scale, out=E, tiles=tiles)
         else:
             mcf.gemm_chain(A, B, D, out=E, tiles=tiles)
@@ -105,6 +120,13 @@ def main():
     prob = c_problem(w.batch, w.M, w.K, w.N, w.L, w.dtype,
                      b_stride=(w.N * w.K, 1, w.K) if w.softmax else None)
     search = None
+    if args.chain3 and tiles is None:
+        try:
+            t3 = mcf.pick_tiles3(prob, P, w.softmax)
+        except mcf.McfError:
+            print(f"bench.py: no three-GEMM kernels built for K={w.K} L={w.L} P={P}", file=sys.stderr)
+            return 2
+        tiles = (t3.mb, t3.rg, t3.ns, t3.nj)
     if args.tune and tiles is None:
         for i in range(max(args.warmup, 3000)):   # bring the clocks up before the first candidate is timed
             step(i)
@@ -176,13 +198,13 @@ def main():
         torch.cuda.synchronize()
 
     gbs = per_set / t_step / 1e9
-    tflops = w.flops / t_step / 1e12
-    ai = w.flops / per_set
+    tflops = flops / t_step / 1e12
+    ai = flops / per_set
     bound = "hbm" if ai < MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9) else "mfma"
     if bound == "hbm":
         achieved, peak, unit = per_set / t_kernel / 1e9, HBM_PEAK_GBS, "GB/s"
     else:
-        achieved, peak, unit = w.flops / t_kernel / 1e12, MFMA_PEAK_TFLOPS, "TFLOP/s"
+        achieved, peak, unit = flops / t_kernel / 1e12, MFMA_PEAK_TFLOPS, "TFLOP/s"
     traffic = None
     if args.traffic and os.path.exists(args.traffic):
         traffic = json.load(open(args.traffic)).get(args.workload)
@@ -191,23 +213,27 @@ def main():
     cpu_baseline, parity = None, None
     if not args.no_cpu_baseline:
         import oracle
-        A, B, D, E = sets[0]
+        A, B, D, E, F = sets[0]
         step(0)
         torch.cuda.synchronize()
-        full_flops = w.flops
+        full_flops = flops
         nb = w.batch if full_flops <= 2.0e10 else max(1, int(w.batch * 2.0e10 / full_flops))
         rows = None
         A64 = mi.from_bits(x["a_bits"][:nb], w.dtype)
         B64 = mi.from_bits(x["b_bits"][:nb], w.dtype)
         B64 = B64.transpose(0, 2, 1) if w.softmax else B64
         D64 = mi.from_bits(x["d_bits"][:nb], w.dtype)
-        if full_flops > 2.0e10:   # long-sequence workload: a bounded sample of rows of one head
+        if full_flops > 2.0e10 and not args.chain3:   # long-sequence workload: a bounded sample of rows of one head
             rng = np.random.default_rng(0)
             n_rows = max(64, int(2.0e10 / (2.0 * w.N * (w.K + w.L))))
             rows = np.stack([np.zeros(n_rows, dtype=np.int64), rng.integers(0, w.M, n_rows)], axis=1)
         tc = time.perf_counter()
         if rows is None:
-            ref, threads = oracle.chain(A64, B64, D64, softmax=w.softmax, scale=w.scale, return_threads=True)
+            if args.chain3:
+                ref, threads = oracle.chain3(A64, B64, D64, mi.from_bits(f_bits[:nb], w.dtype), softmax=w.softmax,
+                                             scale=w.scale, return_threads=True)
+            else:
+                ref, threads = oracle.chain(A64, B64, D64, softmax=w.softmax, scale=w.scale, return_threads=True)
             got = mi.from_bits(E[:nb].contiguous().view(torch.int16).cpu().numpy().view(np.uint16), w.dtype)
             frac = nb / w.batch
             sample = f"all rows of {nb} of {w.batch} batches"
@@ -221,7 +247,7 @@ def main():
         cpu_s = time.perf_counter() - tc
         cpu_baseline = {"value": per_set * frac / cpu_s / 1e9, "unit": "GB/s", "cores": int(threads),
                         "kind": "oracle", "sample": sample, "seconds": cpu_s,
-                        "gflops_fp64": w.flops * frac / cpu_s / 1e9}
+                        "gflops_fp64": flops * frac / cpu_s / 1e9}
         parity = {"max_abs_err": float(np.max(np.abs(got - ref))), "max_abs_ref": float(np.max(np.abs(ref))),
                   "tolerance": 1e-2, "checked": sample}
         parity["ok"] = bool(parity["max_abs_err"] <= 1e-2 * parity["max_abs_ref"])
@@ -232,7 +258,7 @@ def main():
         "ms_per_step": t_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: batch={w.batch} M={w.M} K={w.K} N={w.N} L={w.L} {w.dtype}"
-                               f"{' softmax' if w.softmax else ''}",
+                               f"{' softmax' if w.softmax else ''}{f' + third GEMM P={P}' if args.chain3 else ''}",
                    "tiles": {"mb": picked.mb, "rg": picked.rg, "ns": picked.ns, "nj": picked.nj, "tm": picked.tm,
                              "tn": picked.tn, "tk": picked.tk, "tl": picked.tl, "stages": picked.stages},
                    "buffer_sets": n_sets, "launch": "eager" if args.eager else "hip_graph",

@@ -133,6 +133,28 @@ int mcf_softmax_gemm_chain(const mcf_problem *problem, float scale, const void *
                            const mcf_tiles *tiles_or_null, void *hip_stream);
 
 /*
+ * G = (E) . F with E the chain above, softmax != 0 selecting its softmax form (Sec. III-A: the
+ * analysis "extends to scenarios with more compute-intensive operators"; a chain of three
+ * GEMMs).  F is [batch, L, P] with element strides f_stride {batch, row, col} (NULL or all
+ * zero = packed; col stride 1), G is [batch, M, P] and problem->e_stride describes G (not E,
+ * which never leaves the registers).  E is rounded once to in_dtype before the third GEMM, as
+ * C / P is before the second.  Built for (K, L, P) in {(64,64,64), (128,128,128)}; other
+ * shapes give MCF_EUNSUPPORTED.  tiles_or_null: NULL = the arrangement whose two-GEMM part
+ * the model ranks best among those built for three GEMMs (one wave per row set: ns = 1),
+ * otherwise its mb, rg, ns, nj are read.  G must not overlap A, B, D or F.
+ */
+int mcf_gemm_chain3(const mcf_problem *problem, int softmax, float scale, int64_t P,
+                    const int64_t *f_stride, const void *A, const void *B, const void *D,
+                    const void *F, void *G, const mcf_tiles *tiles_or_null, void *hip_stream);
+
+/* The arrangement mcf_gemm_chain3 takes when given no tiles; the model terms in *out are those
+ * of its two-GEMM part (problem->e_stride is not read).  MCF_EUNSUPPORTED: none built. */
+int mcf_pick_tiles3(const mcf_problem *problem, int64_t P, int softmax, mcf_tiles *out);
+
+/* The (mb, rg, ns, nj) built for the three-GEMM chain of this shape, as mcf_list_variants. */
+int mcf_list_variants3(const mcf_problem *problem, int64_t P, int softmax, int32_t *shapes, int cap);
+
+/*
  * Heuristic search over the built variants (Sec. IV-B, Alg. 1): a population of `population`
  * candidates drawn at random (without repetition while unused ones remain) from the feasible
  * variants (those mcf_list_candidates returns),

@@ -105,7 +105,7 @@ def intermediate_row(A, B, D, b, i, softmax=False, scale=1.0):
     return row[:N]
 
 
-def chain3(A, B, D, F, softmax=False, scale=1.0):
+def chain3(A, B, D, F, softmax=False, scale=1.0, return_threads=False):
     """Three-GEMM chain G = (E) . F with E = chain(A, B, D): F[b,L,P] -> float64 [b,M,P]."""
     (b, M, K, N, L), args, keep = _prep(A, B, D)
     F = np.asarray(F)
@@ -119,7 +119,7 @@ def chain3(A, B, D, F, softmax=False, scale=1.0):
     sf = np.array([s // 8 for s in F.strides], dtype=np.int64)
     G = np.zeros((b, M, P), dtype=np.float64)
     dp, ip = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)
-    _load().mcf_oracle_chain3(*args, int(bool(softmax)), float(scale), P, F.ctypes.data_as(dp),
-                              sf.ctypes.data_as(ip), G.ctypes.data_as(dp))
+    threads = _load().mcf_oracle_chain3(*args, int(bool(softmax)), float(scale), P, F.ctypes.data_as(dp),
+                                        sf.ctypes.data_as(ip), G.ctypes.data_as(dp))
     del keep
-    return G
+    return (G, threads) if return_threads else G

@@ -94,9 +94,14 @@ def load_library():
     lib.mcf_search_tiles.argtypes = [PP, ctypes.c_int, SP, MEASURE_FN, vp, TP, RP]
     lib.mcf_tune_tiles.argtypes = [PP, ctypes.c_int, ctypes.c_float, vp, vp, vp, vp, SP, ctypes.c_int, vp, TP, RP]
     lib.mcf_gemm_chain.argtypes = [PP, vp, vp, vp, vp, TP, vp]
+    lib.mcf_gemm_chain3.argtypes = [PP, ctypes.c_int, ctypes.c_float, ctypes.c_int64, ctypes.POINTER(ctypes.c_int64),
+                                    vp, vp, vp, vp, vp, TP, vp]
+    lib.mcf_pick_tiles3.argtypes = [PP, ctypes.c_int64, ctypes.c_int, TP]
+    lib.mcf_list_variants3.argtypes = [PP, ctypes.c_int64, ctypes.c_int, ctypes.POINTER(ctypes.c_int32), ctypes.c_int]
     lib.mcf_softmax_gemm_chain.argtypes = [PP, ctypes.c_float, vp, vp, vp, vp, TP, vp]
     for f in (lib.mcf_pick_tiles, lib.mcf_eval_tiles, lib.mcf_list_variants, lib.mcf_gemm_chain,
-              lib.mcf_softmax_gemm_chain, lib.mcf_search_tiles, lib.mcf_tune_tiles, lib.mcf_list_candidates):
+              lib.mcf_softmax_gemm_chain, lib.mcf_search_tiles, lib.mcf_tune_tiles, lib.mcf_list_candidates,
+              lib.mcf_gemm_chain3, lib.mcf_list_variants3, lib.mcf_pick_tiles3):
         f.restype = ctypes.c_int
     lib.mcf_status_string.argtypes = [ctypes.c_int]
     lib.mcf_status_string.restype = ctypes.c_char_p
@@ -297,3 +302,67 @@ def tune_tiles(A, B, D, scale=None, out=None, launches=0, population=0, top_n=0,
         ctypes.c_void_p(out.data_ptr()), ctypes.byref(sp), int(launches), _stream_ptr(stream),
         ctypes.byref(best), ctypes.byref(rep)))
     return best, rep
+
+
+def gemm_chain3(A, B, D, F, scale=None, out=None, tiles=None, stream=None):
+    """mcf_gemm_chain3: G = ((A . B) . D) . F, or (softmax_rows(scale * A . B) . D) . F when scale is
+    given, on device tensors; F[b,L,P] with unit column stride, G[b,M,P]."""
+    import torch
+    lib = load_library()
+    if F.dim() != 3 or F.shape[0] != A.shape[0] or F.shape[1] != D.shape[2]:
+        raise McfError(1, f"F{tuple(F.shape)} does not continue D{tuple(D.shape)}")
+    P = F.shape[2]
+    if out is None:
+        out = torch.empty((A.shape[0], A.shape[1], P), dtype=A.dtype, device=A.device)
+    if tuple(out.shape) != (A.shape[0], A.shape[1], P) or not (out.dtype == F.dtype == A.dtype) or out.device != A.device \
+            or F.device != A.device:
+        raise McfError(1, "F and the output must match A in dtype and device, the output be [b, M, P]")
+    # A, B, D as in the two-GEMM chain (a stand-in E of the right shape carries no strides)
+    p = _problem_from_tensors(A, B, D, _MetaLike(A, D))
+    so = list(out.stride()) if out.numel() else [0, 0, 0]
+    if out.shape[0] <= 1:
+        so[0] = 0
+    if out.shape[1] <= 1:
+        so[1] = max(P, 1)
+    for d in range(3):
+        p.e_stride[d] = so[d]
+    sf = list(F.stride()) if F.numel() else [0, 0, 0]
+    if F.shape[0] <= 1:
+        sf[0] = 0
+    fs = (ctypes.c_int64 * 3)(*sf)
+    _check(lib.mcf_gemm_chain3(ctypes.byref(p), int(scale is not None), ctypes.c_float(0.0 if scale is None else scale),
+                               ctypes.c_int64(P), fs, ctypes.c_void_p(A.data_ptr()), ctypes.c_void_p(B.data_ptr()),
+                               ctypes.c_void_p(D.data_ptr()), ctypes.c_void_p(F.data_ptr()), ctypes.c_void_p(out.data_ptr()),
+                               _tiles_arg(tiles), _stream_ptr(stream)))
+    return out
+
+
+class _MetaLike:
+    """Shape / stride stand-in for the E of a three-GEMM chain (it exists only in registers)."""
+
+    def __init__(self, A, D):
+        self.shape = (A.shape[0], A.shape[1], D.shape[2])
+        self.dtype, self.is_cuda, self.device = A.dtype, True, A.device
+
+    def dim(self):
+        return 3
+
+    def numel(self):
+        return 0      # no strides of its own: packed
+
+
+def pick_tiles3(problem, P, softmax=False):
+    """mcf_pick_tiles3: the arrangement gemm_chain3 takes when given no tiles."""
+    lib = load_library()
+    t = Tiles()
+    _check(lib.mcf_pick_tiles3(ctypes.byref(problem), int(P), int(bool(softmax)), ctypes.byref(t)))
+    return t
+
+
+def list_variants3(problem, P, softmax=False):
+    """mcf_list_variants3: (mb, rg, ns, nj) built for the three-GEMM chain of this shape."""
+    lib = load_library()
+    n = lib.mcf_list_variants3(ctypes.byref(problem), int(P), int(bool(softmax)), None, 0)
+    buf = (ctypes.c_int32 * (4 * max(n, 1)))()
+    lib.mcf_list_variants3(ctypes.byref(problem), int(P), int(bool(softmax)), buf, n)
+    return [tuple(buf[4 * i:4 * i + 4]) for i in range(n)]

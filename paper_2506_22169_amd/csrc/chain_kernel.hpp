@@ -34,6 +34,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "mcf_geometry.h"
 #include "mcf_internal.h"
 
@@ -132,7 +134,10 @@ template <int N> static __device__ __forceinline__ void wait_vm() {
 // KSPLIT: KD is the chunk T_K of a k loop inside the block (K = k_chunks * KD); the A chunk of
 // every k step travels through the LDS ring with the B chunk instead of the whole A tile living
 // in registers.
-template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool BKC, bool KSPLIT = false>
+// PD > 0: chain of three GEMMs.  After the n loop the block multiplies its E tile (still in
+// registers) by F[L x PD], which waits in LDS from the prologue on, and stores that product
+// instead of E.  The rows of E must then be complete within a wave: NS = 1.
+template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool BKC, bool KSPLIT = false, int PD = 0>
 __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     using M_ = Mfma<T>;
     using v8 = typename M_::v8;
@@ -140,6 +145,8 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     constexpr int TM = 32 * MB * RG;     // rows per block
     constexpr int TN = 32 * NS * NJ;     // columns per n-iteration
     static_assert(KD % 16 == 0 && LD % 8 == 0, "K in MFMA k-steps of 16, L in 16-byte pieces");
+    constexpr bool CH3 = PD > 0;
+    static_assert(!CH3 || (NS == 1 && !KSPLIT && LD % 32 == 0 && PD % 32 == 0), "three-GEMM chain: one wave per row set");
     constexpr int KS = KD / 16;          // MFMA k-steps of GEMM 1
     constexpr int HB = h_blocks(LD);     // 32-wide h blocks of GEMM 2 (the last may be partial)
     constexpr int KCH = KD / 8, LCH = LD / 8;                  // 16-byte chunks in a row of K / L elements
@@ -162,6 +169,11 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     constexpr int CT = KSPLIT ? (CA + CB > CD ? CA + CB : CD) : CB + CD; // wave-loads of the largest item
     constexpr int PA = (CA + W - 1) / W;
     constexpr int P = (CT + W - 1) / W;
+    // three-GEMM chain: the F tile [LD rows x PD] behind everything else
+    constexpr int RBF = 2 * pitch_elems(CH3 ? PD : 32);
+    constexpr int F_LDS = CH3 ? chain3_f_offset(KD, LD, PD, MB, RG, NJ, S) : 0;
+    constexpr int CF = CH3 ? chain3_f_bytes(LD, PD) / 1024 : 0;
+    constexpr int PFW = (CF + W - 1) / W; // wave-loads of F per wave
     static_assert((S - 1) * P <= 63, "too many loads in flight for the 6-bit vmcnt counter");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_generic[];
@@ -352,6 +364,21 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         }
     };
 
+    // ---- three-GEMM chain: the F tile, first of all loads (it is needed last) ---------------
+    if constexpr (CH3) {
+        const void *fbase = uniform((const void *)((const T *)p.F + batch * p.sf_b));
+        const int sf_r = (int)p.sf_r;
+        const unsigned dst0 = uniform(lds0 + F_LDS + wave * 1024);
+#pragma unroll
+        for (int u = 0; u < PFW; ++u) {
+            const int j = wave + u * W;
+            const int jj = j < CF ? j : CF - 1;
+            const int slot = 64 * jj + lane;
+            int row = slot / (RBF / 16), ch = slot % (RBF / 16);
+            ch ^= swz_tr(RBF, row);
+            dma16(dst0 + (jj - wave) * 1024, (unsigned)(row * sf_r * 2 + ch * 16), fbase);
+        }
+    }
     // ---- prologue: A tile (into the last ring slot) and the first S-1 n-tiles ---------------
     if constexpr (!KSPLIT) {
         const void *abase = uniform((const void *)Ag);
@@ -736,6 +763,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         for (int mb = 0; mb < MB; ++mb) l_run[mb] = xhalf_sum(l_run[mb]);
     }
 
+    if constexpr (CH3) wait_vm<0>(); // the F tile (with N = 0 no loop iteration has waited for it)
     __syncthreads(); // every wave is done reading the ring: its space is reused below
 
     // ---- combine the ns partial results of a row-group -----------------------------------
@@ -815,33 +843,89 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     }
 
     MCF_TRACE_POINT(6);
-    // ---- S_E: E tile -> global ------------------------------------------------------------
-    // Lane (c,g) holds E[row c][32hb + 16g + 0..15] of the blocks its wave owns.  They are
+    float inv[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) inv[mb] = SOFTMAX ? 1.0f / l_run[mb] : 1.0f;
+    constexpr int PB = CH3 ? PD / 32 : 1;
+    f32x16 accO[MB][PB]; // the product E.F of the three-GEMM chain (unused otherwise)
+    if constexpr (CH3) {
+        // ---- third GEMM: G^T[p][m] = sum_h F^T[p][h] E^T[h][m] ----------------------------------
+        // The accumulator of GEMM 2 holds, in lane (c,g), E[row c][32hb + 16g + r]; its registers
+        // 8qp .. 8qp+7, normalised and rounded to 16 bit, are the second MFMA operand for the 16
+        // contraction indices h = 32hb + 16g' + 8qp + e (g' the half-wave, e = 0..7).  The first
+        // operand is read from the F tile with the transposing read, rows h in that order,
+        // columns p mapped as the h of GEMM 2 so that a lane again ends with 16 consecutive p.
+        v8 eop[MB][HB][2];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+                for (int qp = 0; qp < 2; ++qp)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) eop[mb][hb][qp][e] = (T)(accE[mb][hb][8 * qp + e] * inv[mb]);
+        const int x4 = i16 & 3;
+        const int frow = 16 * g + (i16 >> 2); // + 32 hb + 8 qp; upper four contraction indices: + 4 rows
+        const int fch = (u16 + 2 * (x4 & 1)) ^ swz_tr(RBF, frow);
+        const unsigned f_off = (unsigned)(F_LDS + frow * RBF + 16 * fch + 8 * (x4 >> 1)); // p block 0; per pb: ^ (64 pb) bytes
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int pb = 0; pb < PB; ++pb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) accO[mb][pb][r] = 0.f;
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb)
+#pragma unroll
+            for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+                for (int qp = 0; qp < 2; ++qp) {
+                    const lds_u8 *src = smem + (f_off ^ (unsigned)(64 * pb)) + (32 * hb + 8 * qp) * RBF;
+                    i16x4 lo = lds_read_tr(src);
+                    i16x4 hi = lds_read_tr(src + 4 * RBF);
+                    const v8 fop = __builtin_bit_cast(v8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) accO[mb][pb] = M_::run(fop, eop[mb][hb][qp], accO[mb][pb]);
+                }
+    }
+
+    // ---- S_E: output tile -> global ---------------------------------------------------------
+    // Lane (c,g) holds X[row c][32hb + 16g + 0..15] of the blocks its wave owns (X = E, or the
+    // product E.F of the three-GEMM chain; LDX columns).  They are scaled (E by 1 / row sum),
     // staged in LDS (swizzled) and read back so that consecutive lanes store consecutive
     // 16-byte pieces of a row: a store instruction writes whole row segments (whole rows when
     // the wave owns all h blocks of its rows).
-    if (blk0 < NBLK) {
-        static_assert(combine_runs_ok(LD, MB, NS), "a wave's run of blocks straddles row sets");
-        constexpr int HPW = BPW < HB ? BPW : HB;    // h blocks per owned row set
-        constexpr int MPW = BPW < HB ? 1 : BPW / HB; // row sets (of 32 rows) owned
-        constexpr int RBS = estage_row_bytes(LD, MB, NS); // staged row bytes: HPW * 64, rounded up to a power of two
-        constexpr bool EPAD = RBS != HPW * 64 || LPAD; // some staged pieces are padding or lie beyond L
-        const int mb0 = blk0 / HB, h0 = blk0 % HB;
-        lds_u8 *es = smem + combine_bytes(LD, MB, RG, NS) + wave * estage_wave_bytes(LD, MB, NS);
+    constexpr int LDX = CH3 ? PD : LD;
+    constexpr int HBX = h_blocks(LDX);
+    constexpr int BPWX = blocks_per_wave(LDX, MB, NS);
+    const int blk0x = wn * BPWX; // this wave owns blocks [blk0x, blk0x + BPWX) that exist
+    if (blk0x < MB * HBX) {
+        static_assert(combine_runs_ok(LDX, MB, NS), "a wave's run of blocks straddles row sets");
+        constexpr int HPW = BPWX < HBX ? BPWX : HBX;     // h blocks per owned row set
+        constexpr int MPW = BPWX < HBX ? 1 : BPWX / HBX; // row sets (of 32 rows) owned
+        constexpr int RBS = estage_row_bytes(LDX, MB, NS); // staged row bytes: HPW * 64, rounded up to a power of two
+        constexpr bool EPAD = RBS != HPW * 64 || pitch_elems(LDX) != LDX; // some staged pieces are padding or lie beyond the last column
+        const int mb0 = blk0x / HBX, h0 = blk0x % HBX;
+        lds_u8 *es = smem + combine_bytes(LDX, MB, RG, NS) + wave * estage_wave_bytes(LDX, MB, NS);
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-            const float inv = SOFTMAX ? 1.0f / l_run[mb] : 1.0f;
+            const float sc = CH3 ? 1.0f : inv[mb];
 #pragma unroll
-            for (int hb = 0; hb < HB; ++hb) {
-                const int blk = mb * HB + hb;
-                if (blk >= blk0 && blk < blk0 + BPW) {
+            for (int hb = 0; hb < HBX; ++hb) {
+                const int blk = mb * HBX + hb;
+                if (blk >= blk0x && blk < blk0x + BPWX) {
                     const int row = 32 * (mb - mb0) + c;
                     const int sw = swz_b128(RBS, row);
                     v8 lo, hi;
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        lo[e] = (T)(accE[mb][hb][e] * inv);
-                        hi[e] = (T)(accE[mb][hb][8 + e] * inv);
+                        if constexpr (CH3) {
+                            lo[e] = (T)accO[mb][hb][e];
+                            hi[e] = (T)accO[mb][hb][8 + e];
+                        } else {
+                            lo[e] = (T)(accE[mb][hb][e] * sc);
+                            hi[e] = (T)(accE[mb][hb][8 + e] * sc);
+                        }
                     }
                     const int ch = 4 * (hb - h0) + 2 * g;
                     *(lds_u32x4 *)(es + row * RBS + 16 * (ch ^ sw)) = __builtin_bit_cast(u32x4, lo);
@@ -858,7 +942,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             const int row = slot / CPR;
             const int ch = (slot % CPR) ^ swz_b128(RBS, row);
             const u32x4 v = *(const lds_u32x4 *)(es + 16 * slot);
-            if (EPAD && (ch >= 4 * HPW || 32 * h0 + 8 * ch >= LD)) continue;
+            if (EPAD && (ch >= 4 * HPW || 32 * h0 + 8 * ch >= LDX)) continue;
             if (rbase + row < M && (!(MCF_ABLATE & 8) || v[0] == 0x12345u))
                 __builtin_nontemporal_store(v, (u32x4 *)(Eg + (int64_t)(rbase + row) * se_r + 32 * h0 + 8 * ch));
         }
@@ -867,10 +951,18 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
 }
 
 // Host-side launcher of one instantiation.
-template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool BKC, bool KSPLIT = false>
+// LDS bytes of an instantiation.
+template <int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool KSPLIT, int PD>
+constexpr int kernel_lds_bytes() {
+    constexpr int S = ring_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX, KSPLIT);
+    if constexpr (PD > 0) return chain3_lds_bytes(KD, LD, PD, MB, RG, NJ, S);
+    else return total_lds_bytes(KD, LD, MB, RG, NS, NJ, S, KSPLIT);
+}
+
+template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool BKC, bool KSPLIT = false, int PD = 0>
 int launch_chain(const KParams &p, void *stream) {
-    constexpr int lds = total_lds_bytes(KD, LD, MB, RG, NS, NJ, ring_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX, KSPLIT), KSPLIT);
-    auto kern = chain_kernel<T, KD, LD, MB, RG, NS, NJ, SOFTMAX, BKC, KSPLIT>;
+    constexpr int lds = kernel_lds_bytes<KD, LD, MB, RG, NS, NJ, SOFTMAX, KSPLIT, PD>();
+    auto kern = chain_kernel<T, KD, LD, MB, RG, NS, NJ, SOFTMAX, BKC, KSPLIT, PD>;
     // More than 64 KiB of dynamic LDS has to be allowed per function and device, once.  (A race
     // between two threads sets the attribute twice, which is harmless.)
     if (lds > 64 * 1024) {
@@ -891,11 +983,11 @@ int launch_chain(const KParams &p, void *stream) {
 // Launcher of an instantiation, or nullptr when the wave arrangement cannot exist for this
 // (K, L): more LDS than a compute unit has, or (L not a multiple of 32 times a power of two) a
 // wave's run of accumulator blocks would straddle row sets.  Such kernels are not compiled.
-template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool BKC, bool KSPLIT = false>
+template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool BKC, bool KSPLIT = false, int PD = 0>
 constexpr LaunchFn launcher_or_null() {
-    if constexpr (total_lds_bytes(KD, LD, MB, RG, NS, NJ, ring_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX, KSPLIT), KSPLIT) <= kLdsBytesPerBlock &&
-                  combine_runs_ok(LD, MB, NS))
-        return &launch_chain<T, KD, LD, MB, RG, NS, NJ, SOFTMAX, BKC, KSPLIT>;
+    if constexpr (kernel_lds_bytes<KD, LD, MB, RG, NS, NJ, SOFTMAX, KSPLIT, PD>() <= kLdsBytesPerBlock &&
+                  combine_runs_ok(LD, MB, NS) && (PD == 0 || NS == 1))
+        return &launch_chain<T, KD, LD, MB, RG, NS, NJ, SOFTMAX, BKC, KSPLIT, PD>;
     else
         return nullptr;
 }

@@ -69,38 +69,102 @@ static bool overlaps(const void *x, int64_t xe, const void *y, int64_t ye) {
     return xe > 0 && ye > 0 && a < b + 2 * ye && b < a + 2 * xe;
 }
 
-static int run(const mcf_problem *p, int softmax, float scale, const void *A, const void *B, const void *D, void *E,
-               const mcf_tiles *tiles, void *stream) {
+// Variant of the three-GEMM chain for (dtype, K, L, P) and an arrangement, or nullptr.
+static const Variant *find_variant3(int dtype, int64_t K, int64_t L, int64_t P, int softmax, int b_kcontig, int mb, int rg,
+                                    int ns, int nj) {
+    int n = 0;
+    const Variant *v = variants3(&n);
+    for (int i = 0; i < n; ++i)
+        if (v[i].dtype == dtype && v[i].K == K && v[i].L == L && v[i].P == P && v[i].softmax == softmax &&
+            v[i].b_kcontig == b_kcontig && v[i].mb == mb && v[i].rg == rg && v[i].ns == ns && v[i].nj == nj)
+            return &v[i];
+    return nullptr;
+}
+
+// Tile choice for the three-GEMM chain: the arrangement (among those built for it) whose
+// two-GEMM part the model ranks best (ties: the larger nj, as in the two-GEMM ranking); the
+// third GEMM adds the same work to each of them.
+static int pick3(const mcf_problem *p, int softmax, int b_kcontig, int64_t P, mcf_tiles *out) {
+    int n = 0;
+    const Variant *v = variants3(&n);
+    bool have = false;
+    for (int i = 0; i < n; ++i) {
+        if (v[i].dtype != p->in_dtype || v[i].K != p->K || v[i].L != p->L || v[i].P != P ||
+            v[i].softmax != (softmax != 0) || v[i].b_kcontig != b_kcontig || v[i].scratch_bytes != 0)
+            continue;
+        mcf_tiles t;
+        memset(&t, 0, sizeof(t));
+        t.mb = v[i].mb; t.rg = v[i].rg; t.ns = v[i].ns; t.nj = v[i].nj;
+        const int st = mcf_eval_tiles(p, softmax, &t);
+        if (st != MCF_OK && st != MCF_EINVAL) continue;
+        if (!have || t.t_est_s < out->t_est_s || (t.t_est_s == out->t_est_s && t.nj > out->nj)) { *out = t; have = true; }
+    }
+    return have ? MCF_OK : MCF_EUNSUPPORTED;
+}
+
+// P == 0: the two-GEMM chain into E[b, M, L].  P > 0: the three-GEMM chain; F[b, L, P] with
+// strides fstr (all zero = packed), and E / e_stride describe the output [b, M, P].
+static int run(const mcf_problem *p_in, int softmax, float scale, const void *A, const void *B, const void *D, void *E,
+               const mcf_tiles *tiles, void *stream, int64_t P = 0, const int64_t *fstr = nullptr,
+               const void *F = nullptr) {
     set_last_error("");
-    if (!p) return MCF_EINVAL;
-    if (p->batch < 0 || p->M < 0 || p->K < 0 || p->N < 0 || p->L < 0) return MCF_EINVAL;
+    if (!p_in) return MCF_EINVAL;
+    mcf_problem pc = *p_in;
+    const mcf_problem *p = &pc;
+    if (p->batch < 0 || p->M < 0 || p->K < 0 || p->N < 0 || p->L < 0 || P < 0) return MCF_EINVAL;
+    const bool ch3 = P > 0;
+    int64_t sg[3] = {0, 0, 0}, sf[3] = {0, 0, 0};
+    if (ch3) {
+        // A, B, D are laid out as in the two-GEMM chain; the output and F are checked here
+        memcpy(sg, p->e_stride, sizeof(sg));
+        memset(pc.e_stride, 0, sizeof(pc.e_stride));
+        if (all_zero(sg)) packed(sg, p->M, P);
+        if (fstr) memcpy(sf, fstr, sizeof(sf));
+        if (all_zero(sf)) packed(sf, p->L, P);
+        for (int d = 0; d < 3; ++d)
+            if (sg[d] < 0 || sf[d] < 0) return MCF_EINVAL;
+        if (sg[2] != 1 || sf[2] != 1) return MCF_EUNSUPPORTED;
+        if ((p->M > 1 && sg[1] < P) || (p->L > 1 && sf[1] < P)) return MCF_EINVAL;
+        if (sg[1] % 8 || sg[0] % 8 || sf[1] % 8 || sf[0] % 8) return MCF_EALIGN;
+        if (sg[1] >= (1ll << 21) || sf[1] >= (1ll << 21)) return MCF_EUNSUPPORTED;
+    }
     Layout lay;
     int st = decode_layout(p, &lay);
     if (st != MCF_OK) return st;
+    if (ch3) memcpy(lay.se, sg, sizeof(sg));
     if (softmax && !(scale == scale && fabsf(scale) <= 3.0e38f)) return MCF_EINVAL; // NaN / inf scale
     if (p->batch == 0 || p->M == 0 || p->L == 0) return MCF_OK;
     if (softmax && p->N == 0) return MCF_EINVAL;
-    if (!A || !E || (p->N > 0 && (!B || !D))) return MCF_EINVAL;
+    if (!A || !E || (p->N > 0 && (!B || !D)) || (ch3 && !F)) return MCF_EINVAL;
 
     const int64_t ea = span(p->batch, p->M, p->K, lay.sa), eb = span(p->batch, p->K, p->N, lay.sb);
-    const int64_t ed = span(p->batch, p->N, p->L, lay.sd), ee = span(p->batch, p->M, p->L, lay.se);
-    if (overlaps(E, ee, A, ea) || overlaps(E, ee, B, eb) || overlaps(E, ee, D, ed)) return MCF_EINVAL;
-    const uintptr_t ptrs[4] = {(uintptr_t)A, (uintptr_t)B, (uintptr_t)D, (uintptr_t)E};
-    for (int t = 0; t < 4; ++t)
+    const int64_t ed = span(p->batch, p->N, p->L, lay.sd), ee = span(p->batch, p->M, ch3 ? P : p->L, lay.se);
+    const int64_t ef = ch3 ? span(p->batch, p->L, P, sf) : 0;
+    if (overlaps(E, ee, A, ea) || overlaps(E, ee, B, eb) || overlaps(E, ee, D, ed) || (ch3 && overlaps(E, ee, F, ef)))
+        return MCF_EINVAL;
+    const uintptr_t ptrs[5] = {(uintptr_t)A, (uintptr_t)B, (uintptr_t)D, (uintptr_t)E, (uintptr_t)F};
+    for (int t = 0; t < 5; ++t)
         if (ptrs[t] % 16 != 0) return MCF_EALIGN;
 
     mcf_tiles chosen;
     if (tiles) {
         chosen = *tiles;
     } else {
-        st = mcf_pick_tiles(p, softmax, &chosen);
+        st = ch3 ? pick3(p, softmax, lay.b_kcontig, P, &chosen) : mcf_pick_tiles(p, softmax, &chosen);
         if (st != MCF_OK) return st;
     }
-    const int64_t tl = chosen.tl > 0 ? chosen.tl : p->L;
+    const int64_t tl = ch3 ? p->L : (chosen.tl > 0 ? chosen.tl : p->L);
     if (p->L % tl != 0) return MCF_EINVAL;
-    const Variant *v = find_variant(p->in_dtype, p->K, tl, softmax, lay.b_kcontig, chosen.mb, chosen.rg, chosen.ns, chosen.nj > 0 ? chosen.nj : 1);
-    if (!v) return tiles ? MCF_EINVAL : MCF_EUNSUPPORTED;
-    if (lds_bytes_for(v) > kLdsBytesPerBlock)
+    const int nj_ = chosen.nj > 0 ? chosen.nj : 1;
+    const Variant *v = ch3 ? find_variant3(p->in_dtype, p->K, p->L, P, softmax, lay.b_kcontig, chosen.mb, chosen.rg, chosen.ns, nj_)
+                           : find_variant(p->in_dtype, p->K, tl, softmax, lay.b_kcontig, chosen.mb, chosen.rg, chosen.ns, nj_);
+    if (!v) {
+        if (!ch3) return tiles ? MCF_EINVAL : MCF_EUNSUPPORTED;
+        // no kernels for this (K, L, P) at all, or only this arrangement is missing?
+        mcf_tiles any;
+        return pick3(p, softmax, lay.b_kcontig, P, &any) == MCF_OK ? MCF_EINVAL : MCF_EUNSUPPORTED;
+    }
+    if (!ch3 && lds_bytes_for(v) > kLdsBytesPerBlock)
         return MCF_EINVAL; // more LDS than a compute unit has
 
     const int64_t tm = 32ll * v->mb * v->rg;
@@ -121,6 +185,7 @@ static int run(const mcf_problem *p, int softmax, float scale, const void *A, co
     k.n_blocks = (int32_t)(p->batch * m_tiles * h_tiles);
     k.c1 = 1.0f; k.a_mode = 0;
     k.k_chunks = (int32_t)(p->K / v->K);
+    k.F = F; k.sf_b = sf[0]; k.sf_r = sf[1];
     if (softmax) {
         // exp(scale*s - max) = exp2(|scale|*log2(e) * (s' - max')) with s' = +-s; a zero scale
         // makes every logit equal, which is what A := 0 gives.
@@ -146,6 +211,43 @@ extern "C" int mcf_gemm_chain(const mcf_problem *p, const void *A, const void *B
 extern "C" int mcf_softmax_gemm_chain(const mcf_problem *p, float scale, const void *A, const void *B, const void *D,
                                       void *E, const mcf_tiles *tiles, void *stream) {
     return mcf::run(p, 1, scale, A, B, D, E, tiles, stream);
+}
+
+extern "C" int mcf_gemm_chain3(const mcf_problem *p, int softmax, float scale, int64_t P, const int64_t *f_stride,
+                               const void *A, const void *B, const void *D, const void *F, void *G,
+                               const mcf_tiles *tiles, void *stream) {
+    if (P <= 0) return P == 0 && p && p->batch >= 0 ? MCF_OK : MCF_EINVAL; // no output columns: nothing to do
+    return mcf::run(p, softmax != 0, softmax ? scale : 1.0f, A, B, D, G, tiles, stream, P, f_stride, F);
+}
+
+extern "C" int mcf_pick_tiles3(const mcf_problem *p, int64_t P, int softmax, mcf_tiles *out) {
+    mcf::Layout lay;
+    if (!p || !out || P <= 0) return MCF_EINVAL;
+    mcf_problem pc = *p;
+    memset(pc.e_stride, 0, sizeof(pc.e_stride)); // describes G, which the tile choice does not depend on
+    const int st = mcf::decode_layout(&pc, &lay);
+    if (st != MCF_OK) return st;
+    return mcf::pick3(&pc, softmax != 0, lay.b_kcontig, P, out);
+}
+
+extern "C" int mcf_list_variants3(const mcf_problem *p, int64_t P, int softmax, int32_t *out, int cap) {
+    mcf::Layout lay;
+    if (!p) return 0;
+    mcf_problem pc = *p;
+    memset(pc.e_stride, 0, sizeof(pc.e_stride));
+    if (mcf::decode_layout(&pc, &lay) != MCF_OK) return 0;
+    int n = 0, total = 0;
+    const mcf::Variant *v = mcf::variants3(&n);
+    for (int i = 0; i < n; ++i) {
+        if (v[i].dtype != p->in_dtype || v[i].K != p->K || v[i].L != p->L || v[i].P != P ||
+            v[i].softmax != (softmax != 0) || v[i].b_kcontig != lay.b_kcontig)
+            continue;
+        if (out && total < cap) {
+            out[4 * total] = v[i].mb; out[4 * total + 1] = v[i].rg; out[4 * total + 2] = v[i].ns; out[4 * total + 3] = v[i].nj;
+        }
+        ++total;
+    }
+    return total;
 }
 
 extern "C" const char *mcf_status_string(int s) {

@@ -42,6 +42,15 @@
     X(2, 2, 2, 1)            \
     X(2, 1, 4, 1)
 
+// Arrangements built for the three-GEMM chain (one wave per row set: ns = 1).
+#define MCF_CHAIN3_SHAPES(X) \
+    X(1, 4, 1, 1)            \
+    X(1, 4, 1, 2)            \
+    X(1, 8, 1, 1)            \
+    X(1, 8, 1, 2)            \
+    X(2, 4, 1, 1)            \
+    X(2, 4, 1, 2)
+
 namespace mcf {
 
 // The variant table of one (dtype, K, L) group; arrangements that cannot exist for this
@@ -49,7 +58,7 @@ namespace mcf {
 template <typename T, int DT, int K, int L, bool KSPLIT>
 const Variant *group_table(int *count) {
 #define MCF_ROW(mb, rg, ns, nj, sm, bkc) \
-    {DT, K, L, mb, rg, ns, nj, sm, bkc, KSPLIT, launcher_or_null<T, K, L, mb, rg, ns, nj, sm, bkc, KSPLIT>()},
+    {DT, K, L, mb, rg, ns, nj, sm, bkc, KSPLIT, 0, launcher_or_null<T, K, L, mb, rg, ns, nj, sm, bkc, KSPLIT>()},
 #define MCF_X(mb, rg, ns, nj)             \
     MCF_ROW(mb, rg, ns, nj, false, false) \
     MCF_ROW(mb, rg, ns, nj, false, true)  \
@@ -68,12 +77,33 @@ const Variant *group_table(int *count) {
 #undef MCF_ROW
 }
 
+// The variant table of one (dtype, K, L, P) group of the three-GEMM chain.
+template <typename T, int DT, int K, int L, int P>
+const Variant *group_table3(int *count) {
+#define MCF_ROW(mb, rg, ns, nj, sm, bkc) \
+    {DT, K, L, mb, rg, ns, nj, sm, bkc, 0, P, launcher_or_null<T, K, L, mb, rg, ns, nj, sm, bkc, false, P>()},
+#define MCF_X(mb, rg, ns, nj)             \
+    MCF_ROW(mb, rg, ns, nj, false, false) \
+    MCF_ROW(mb, rg, ns, nj, false, true)  \
+    MCF_ROW(mb, rg, ns, nj, true, false)  \
+    MCF_ROW(mb, rg, ns, nj, true, true)
+    static const Variant table[] = {MCF_CHAIN3_SHAPES(MCF_X)};
+    *count = (int)(sizeof(table) / sizeof(table[0]));
+    return table;
+#undef MCF_X
+#undef MCF_ROW
+}
+
 } // namespace mcf
 
 // One per instantiation file: defines mcf::variants_<NAME>(int*).
 #define MCF_DEFINE_GROUP(T, DT, K, L, NAME)                                                        \
     namespace mcf {                                                                                \
     const Variant *variants_##NAME(int *count) { return group_table<T, DT, K, L, false>(count); }  \
+    }
+#define MCF_DEFINE_CHAIN3_GROUP(T, DT, K, L, P, NAME)                                              \
+    namespace mcf {                                                                                \
+    const Variant *variants_##NAME(int *count) { return group_table3<T, DT, K, L, P>(count); }     \
     }
 #define MCF_DEFINE_KSPLIT_GROUP(T, DT, TK, L, NAME)                                                \
     namespace mcf {                                                                                \

@@ -34,6 +34,8 @@ struct KParams {
     float c1;           // |scale| * log2(e) (softmax only)
     int32_t a_mode;     // 0: A as is, 1: -A (negative scale), 2: A := 0 (scale == 0)
     int32_t k_chunks;   // kernels with a k loop: K / T_K (otherwise unused)
+    const void *F;      // three-GEMM chain: F[b, L, P] (col stride 1); E is then the output [b, M, P]
+    int64_t sf_b, sf_r; // F: batch / row stride
 };
 
 typedef int (*LaunchFn)(const KParams &p, void *stream); // returns hipError_t as int
@@ -43,13 +45,16 @@ struct Variant {
     int32_t mb, rg, ns, nj;
     int32_t softmax, b_kcontig;
     int32_t ksplit;        // 1: K is the chunk T_K of a k loop inside the block; 0: T_K = K
+    int32_t P;             // three-GEMM chain: columns of F and of the output; 0: two-GEMM chain
     LaunchFn launch;
     int32_t vgprs;         // VGPRs per lane the compiler allocated (-1: unknown)
     int32_t scratch_bytes; // per-lane scratch (register spills); such variants are never picked
 };
 
-// Registry of every built kernel variant (defined in mcf_registry.cpp).
+// Registry of every built kernel variant (defined in mcf_registry.cpp): the two-GEMM chain ...
 const Variant *variants(int *count);
+// ... and the three-GEMM chain (P > 0).
+const Variant *variants3(int *count);
 // The kernel group that serves a problem's (dtype, K, L): the group with T_K = K if it is built,
 // otherwise a group with a k loop whose chunk divides K.  Returns false if there is neither;
 // *tk is the K of the group's variants, *ksplit whether they loop over k.

@@ -10,20 +10,19 @@ namespace mcf {
     X(bf16_32_32) X(bf16_64_64) X(bf16_128_128) X(bf16_64_128) X(bf16_128_64) X(bf16_64_256) X(bf16_256_256)      \
     X(f16_k128x_64) X(f16_k128x_128) X(f16_k128x_256) X(bf16_k128x_64) X(bf16_k128x_128) X(bf16_k128x_256)      \
     X(f16_80_80) X(bf16_80_80)
+#define MCF_GROUPS3(X) X(f16_c3_64_64_64) X(f16_c3_128_128_128) X(bf16_c3_64_64_64) X(bf16_c3_128_128_128)
 #define MCF_DECL(NAME) const Variant *variants_##NAME(int *count);
 MCF_GROUPS(MCF_DECL)
+MCF_GROUPS3(MCF_DECL)
 
 // Registers / scratch of every kernel as the compiler built it (generated at build time).
 struct Resources {
-    int dtype, K, L, mb, rg, ns, nj, softmax, b_kcontig, ksplit, vgprs, sgprs, scratch_bytes;
+    int dtype, K, L, mb, rg, ns, nj, softmax, b_kcontig, ksplit, P, vgprs, sgprs, scratch_bytes;
 };
 static const Resources kResources[] = {
 #include "mcf_resources.inc"
 };
 
-static const std::vector<Variant> &all() {
-    static const std::vector<Variant> table = [] {
-        std::vector<Variant> t;
 #define MCF_ADD(NAME)                                    \
     {                                                    \
         int n = 0;                                       \
@@ -31,20 +30,43 @@ static const std::vector<Variant> &all() {
         for (int i = 0; i < n; ++i)                      \
             if (v[i].launch) t.push_back(v[i]);          \
     }
+static void attach_resources(std::vector<Variant> &t) {
+    for (Variant &v : t) {
+        v.vgprs = -1;
+        v.scratch_bytes = 0;
+        for (const Resources &r : kResources)
+            if (r.dtype == v.dtype && r.K == v.K && r.L == v.L && r.mb == v.mb && r.rg == v.rg && r.ns == v.ns &&
+                r.nj == v.nj && r.softmax == v.softmax && r.b_kcontig == v.b_kcontig && r.ksplit == v.ksplit && r.P == v.P) {
+                v.vgprs = r.vgprs;
+                v.scratch_bytes = r.scratch_bytes;
+            }
+    }
+}
+
+static const std::vector<Variant> &all() {
+    static const std::vector<Variant> table = [] {
+        std::vector<Variant> t;
         MCF_GROUPS(MCF_ADD)
-        for (Variant &v : t) {
-            v.vgprs = -1;
-            v.scratch_bytes = 0;
-            for (const Resources &r : kResources)
-                if (r.dtype == v.dtype && r.K == v.K && r.L == v.L && r.mb == v.mb && r.rg == v.rg && r.ns == v.ns &&
-                    r.nj == v.nj && r.softmax == v.softmax && r.b_kcontig == v.b_kcontig && r.ksplit == v.ksplit) {
-                    v.vgprs = r.vgprs;
-                    v.scratch_bytes = r.scratch_bytes;
-                }
-        }
+        attach_resources(t);
         return t;
     }();
     return table;
+}
+
+static const std::vector<Variant> &all3() {
+    static const std::vector<Variant> table = [] {
+        std::vector<Variant> t;
+        MCF_GROUPS3(MCF_ADD)
+        attach_resources(t);
+        return t;
+    }();
+    return table;
+}
+
+const Variant *variants3(int *count) {
+    const auto &t = all3();
+    *count = (int)t.size();
+    return t.data();
 }
 
 const Variant *variants(int *count) {

@@ -171,3 +171,29 @@ def test_rule3_fallback_and_ragged_shapes():
     # the number of blocks drives alpha: a single small batch prefers the smallest m-tile
     t = mcf.pick_tiles(make_problem(1, 1024, 64, 128, 64, "f16"))
     assert t.tm == 32
+
+
+def test_three_gemm_chain_host_side():
+    """Arrangements built for the three-GEMM chain: one wave per row set (ns = 1), for
+    (K, L, P) in {(64,64,64), (128,128,128)}; the default pick is one of them, the one with the
+    smallest two-GEMM estimate, the larger nj on a tie; other shapes are refused."""
+    for K in (64, 128):
+        for dtype in ("f16", "bf16"):
+            for softmax in (False, True):
+                prob = make_problem(8, 1024, K, 1024, K, dtype, b_stride=(1024 * K, 1, K) if softmax else None)
+                shapes = mcf.list_variants3(prob, K, softmax)
+                assert len(shapes) >= 6 and all(s[2] == 1 for s in shapes)
+                assert set(shapes) <= set(mcf.list_variants(prob, softmax))
+                t = mcf.pick_tiles3(prob, K, softmax)
+                assert (t.mb, t.rg, t.ns, t.nj) in shapes
+                ests = {s: mcf.eval_tiles(prob, *s, softmax=softmax).t_est_s for s in shapes}
+                assert t.t_est_s == min(ests.values())
+                assert t.nj == max(s[3] for s in shapes if ests[s] == t.t_est_s)
+    prob = make_problem(8, 1024, 64, 1024, 64, "f16")
+    assert mcf.list_variants3(prob, 32, False) == []
+    with pytest.raises(mcf.McfError) as e:
+        mcf.pick_tiles3(prob, 128, False)
+    assert e.value.status == 2
+    with pytest.raises(mcf.McfError) as e:
+        mcf.pick_tiles3(make_problem(8, 1024, 32, 1024, 32, "f16"), 32, False)
+    assert e.value.status == 2
