@@ -251,3 +251,50 @@ def test_random_shapes_strides_and_tiles():
         outside[:, :M, :L] = 5.0
         assert bool((outside == 5.0).all()), f"case {case}: wrote outside the output view"
     print(f"worst max|err|/max|oracle| = {worst:.3e}", flush=True)
+
+
+@pytest.mark.parametrize("softmax", [False, True])
+def test_maximum_sizes_sampled(softmax):
+    """Extents near the top of what one launch takes: more than 2^31 bytes of A and of E (the
+    addresses need 64 bits), a quarter of a million blocks, and a batch count of 200 000.
+    The long operand is drawn on the device by torch's seeded generator; the oracle sees the
+    sampled rows of it copied back, and computes those rows one by one."""
+    K = L = 64 if softmax else 32
+    dtype, tdt = ("bf16", torch.bfloat16) if softmax else ("f16", torch.float16)
+    M = (1 << 31) // (2 * K) + 37                      # row 2^31 / (2K) starts at byte offset 2^31
+    N = 72
+    gen = torch.Generator(device="cuda").manual_seed(777 + K)
+    A = torch.empty((1, M, K), dtype=tdt, device="cuda")
+    step = 1 << 22
+    for r0 in range(0, M, step):                       # in pieces: no fp32 copy of the whole tensor
+        A[0, r0:r0 + step] = torch.randn((min(step, M - r0), K), generator=gen, device="cuda").to(tdt)
+    w = mi.make_problem(1, 8, K, N, L, dtype, softmax, "normal", seed=778)   # B and D from the usual recipe
+    x = mi.make_inputs(w)
+    _, B, D = device_inputs(w, x)
+    print(f"case maximum sizes softmax={softmax} M={M}", flush=True)
+    E = mcf.softmax_gemm_chain(A, B, D, w.scale) if softmax else mcf.gemm_chain(A, B, D)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(9)
+    edge = (1 << 31) // (2 * K)
+    rows = np.unique(np.concatenate([rng.integers(0, M, 400), np.arange(0, 40), np.arange(M - 40, M),
+                                     np.arange(edge - 40, edge + 37)]))
+    idx = torch.from_numpy(rows).cuda()
+    A64 = to_host64(A[0, idx].unsqueeze(0), dtype)
+    sel = np.stack([np.zeros(len(rows), dtype=np.int64), np.arange(len(rows))], axis=1)
+    ref = oracle.chain_rows(A64, x["B"], x["D"], sel, softmax=softmax, scale=w.scale)
+    got = to_host64(E[0, idx], dtype)
+    assert np.max(np.abs(got - ref)) <= TOL * np.max(np.abs(ref))
+    del A, E
+    # many batches of a few rows each
+    b = 200_000
+    A = torch.randn((b, 8, K), generator=gen, device="cuda").to(tdt)
+    Bb = torch.randn((b, N, K) if softmax else (b, K, N), generator=gen, device="cuda").to(tdt)
+    Bb = Bb.transpose(1, 2) if softmax else Bb
+    Db = torch.randn((b, N, L), generator=gen, device="cuda").to(tdt)
+    print(f"case many batches softmax={softmax} batch={b}", flush=True)
+    E = mcf.softmax_gemm_chain(A, Bb, Db, w.scale) if softmax else mcf.gemm_chain(A, Bb, Db)
+    torch.cuda.synchronize()
+    pick = torch.from_numpy(np.unique(np.concatenate([rng.integers(0, b, 60), [0, b - 1]]))).cuda()
+    ref = oracle.chain(to_host64(A[pick], dtype), to_host64(Bb[pick], dtype), to_host64(Db[pick], dtype),
+                       softmax=softmax, scale=w.scale)
+    assert np.max(np.abs(to_host64(E[pick], dtype) - ref)) <= TOL * np.max(np.abs(ref))
