@@ -405,7 +405,11 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     MCF_TRACE_POINT(1);
 
     // ---- L_A: A tile (or chunk) in LDS -> registers, as the second MFMA operand A^T[k][m] ---
+    // a_mode (softmax only: a negative or zero scale) as two masks, so that a kernel with a k
+    // loop, which runs this once per chunk, pays two operations per register and a plain chain none.
     v8 a[MB][KS];
+    const unsigned a_flip = (SOFTMAX && a_mode == 1) ? 0x80008000u : 0u; // sign bits of both 16-bit floats
+    const unsigned a_keep = (SOFTMAX && a_mode == 2) ? 0u : 0xffffffffu;
     auto load_a = [&](unsigned base) __attribute__((always_inline)) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
@@ -415,8 +419,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 u32x4 raw = *(const lds_u32x4 *)(src + 16 * ((2 * ks + g) ^ sw));
-                if (a_mode == 1) raw ^= 0x80008000u; // flip the sign of all eight 16-bit floats
-                if (a_mode == 2) raw = u32x4{0u, 0u, 0u, 0u};
+                if constexpr (SOFTMAX) raw = (raw ^ a_flip) & a_keep;
                 a[mb][ks] = __builtin_bit_cast(v8, raw);
             }
         }
