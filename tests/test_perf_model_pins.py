@@ -26,6 +26,23 @@ def test_search_space_size():
     assert pm.n_candidates(1024, 1024, 512, 512) == G["n_candidates_M1024_N1024_K512_H512"]["value"]
 
 
+def test_rule3_discards_what_the_paper_says():
+    """Sec. III-C on the example M = N = 1024, K = H = 512: of the multiples of 16, Rule 3 keeps only
+    the tile sizes that divide their (power-of-two) dimension, i.e. discards 99 % of the choices."""
+    dims = (1024, 1024, 512, 512)
+    kept = 1
+    for d in dims:
+        ok = [t for t in range(16, d + 1, 16) if pm.padding_ok(d, t)]
+        assert ok == [t for t in (16, 32, 64, 128, 256, 512, 1024) if t <= d]     # the divisors, nothing else
+        kept *= len(ok)
+    total = pm.n_candidates(*dims) // (len(pm.deep_tilings()) + len(pm.flat_tilings()))
+    assert kept == 7 * 7 * 6 * 6
+    assert 1.0 - kept / total >= G["rule3_discard_fraction_min"]["value"]
+    # a dimension that is not a power of two: padding below 5 % is allowed (S8: M = 768)
+    assert pm.padding_ok(768, 256) and pm.padding_ok(768, 128) and not pm.padding_ok(768, 512)
+    assert pm.padding_ok(1000, 32) and not pm.padding_ok(1000, 96)   # 1024/1000 - 1 = 2.4 %; 1056/1000 - 1 = 5.6 %
+
+
 def test_hoisting_factors_of_mhnk():
     ext = {"m": 8, "h": 3, "n": 5, "k": 4}
     # default association: every statement of C_C in m,h,n,k; those of C_E in m,h,n
