@@ -134,14 +134,15 @@ int mcf_softmax_gemm_chain(const mcf_problem *problem, float scale, const void *
 
 /*
  * G = (E) . F with E the chain above, softmax != 0 selecting its softmax form (Sec. III-A: the
- * analysis "extends to scenarios with more compute-intensive operators"; a chain of three
- * GEMMs).  F is [batch, L, P] with element strides f_stride {batch, row, col} (NULL or all
- * zero = packed; col stride 1), G is [batch, M, P] and problem->e_stride describes G (not E,
- * which never leaves the registers).  E is rounded once to in_dtype before the third GEMM, as
- * C / P is before the second.  Built for (K, L, P) in {(64,64,64), (128,128,128)}; other
+ * paper's analysis carries over to chains with more compute-intensive operators; this is the
+ * chain of three GEMMs).  F is [batch, L, P] with element strides f_stride {batch, row, col}
+ * (NULL or all zero = packed; col stride 1), G is [batch, M, P] and problem->e_stride
+ * describes G (not E, which never leaves the registers).  E is rounded once to in_dtype
+ * before the third GEMM, as C / P is before the second (with a split of n across waves: each
+ * wave's normalised partial E).  Built for (K, L, P) in {(64,64,64), (128,128,128)}; other
  * shapes give MCF_EUNSUPPORTED.  tiles_or_null: NULL = the arrangement whose two-GEMM part
- * the model ranks best among those built for three GEMMs (one wave per row set: ns = 1),
- * otherwise its mb, rg, ns, nj are read.  G must not overlap A, B, D or F.
+ * the model ranks best among those built for three GEMMs, otherwise its mb, rg, ns, nj are
+ * read.  G must not overlap A, B, D or F.
  */
 int mcf_gemm_chain3(const mcf_problem *problem, int softmax, float scale, int64_t P,
                     const int64_t *f_stride, const void *A, const void *B, const void *D,

@@ -146,7 +146,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     constexpr int TN = 32 * NS * NJ;     // columns per n-iteration
     static_assert(KD % 16 == 0 && LD % 8 == 0, "K in MFMA k-steps of 16, L in 16-byte pieces");
     constexpr bool CH3 = PD > 0;
-    static_assert(!CH3 || (NS == 1 && !KSPLIT && LD % 32 == 0 && PD % 32 == 0), "three-GEMM chain: one wave per row set");
+    static_assert(!CH3 || ((NS == 1 || PD == LD) && !KSPLIT && LD % 32 == 0 && PD % 32 == 0), "three-GEMM chain: whole 32-column blocks; with ns > 1 the product has the shape of E");
     constexpr int KS = KD / 16;          // MFMA k-steps of GEMM 1
     constexpr int HB = h_blocks(LD);     // 32-wide h blocks of GEMM 2 (the last may be partial)
     constexpr int KCH = KD / 8, LCH = LD / 8;                  // 16-byte chunks in a row of K / L elements
@@ -171,7 +171,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     constexpr int P = (CT + W - 1) / W;
     // three-GEMM chain: the F tile [LD rows x PD] behind everything else
     constexpr int RBF = 2 * pitch_elems(CH3 ? PD : 32);
-    constexpr int F_LDS = CH3 ? chain3_f_offset(KD, LD, PD, MB, RG, NJ, S) : 0;
+    constexpr int F_LDS = CH3 ? chain3_f_offset(KD, LD, PD, MB, RG, NS, NJ, S) : 0;
     constexpr int CF = CH3 ? chain3_f_bytes(LD, PD) / 1024 : 0;
     constexpr int PFW = (CF + W - 1) / W; // wave-loads of F per wave
     static_assert((S - 1) * P <= 63, "too many loads in flight for the 6-bit vmcnt counter");
@@ -769,6 +769,63 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     if constexpr (CH3) wait_vm<0>(); // the F tile (with N = 0 no loop iteration has waited for it)
     __syncthreads(); // every wave is done reading the ring: its space is reused below
 
+    // ---- third GEMM: G^T[p][m] = sum_h F^T[p][h] E^T[h][m] --------------------------------------
+    // It is linear in E, so with ns > 1 every wave applies it to its own partial E (of its n
+    // slice) and the partial products are combined below exactly as the partial E would be.
+    // The accumulator of GEMM 2 holds, in lane (c,g), E[row c][32hb + 16g + r]; its registers
+    // 8qp .. 8qp+7, scaled and rounded to 16 bit, are the second MFMA operand for the 16
+    // contraction indices h = 32hb + 16g' + 8qp + e (g' the half-wave, e = 0..7).  The first
+    // operand is read from the F tile with the transposing read, rows h in that order,
+    // columns p mapped as the h of GEMM 2 so that a lane again ends with 16 consecutive p.
+    // Softmax: the partial E is divided by the wave's own row sum before the rounding (it is
+    // then a convex combination of rows of D, whatever the sum), and the combine weighs the
+    // waves by f_w * l_w instead of f_w.
+    constexpr int PB = CH3 ? PD / 32 : 1;
+    f32x16 accO[MB][PB]; // the product E.F (unused otherwise)
+    if constexpr (CH3) {
+        static_assert(NS == 1 || PD == LD, "the combine of the product reuses the layout of E");
+        v8 eop[MB][HB][2];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            const float inv_w = SOFTMAX ? (l_run[mb] > 0.f ? 1.0f / l_run[mb] : 0.f) : 1.0f;
+#pragma unroll
+            for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+                for (int qp = 0; qp < 2; ++qp)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) eop[mb][hb][qp][e] = (T)(accE[mb][hb][8 * qp + e] * inv_w);
+        }
+        const int x4 = i16 & 3;
+        const int frow = 16 * g + (i16 >> 2); // + 32 hb + 8 qp; upper four contraction indices: + 4 rows
+        const int fch = (u16 + 2 * (x4 & 1)) ^ swz_tr(RBF, frow);
+        const unsigned f_off = (unsigned)(F_LDS + frow * RBF + 16 * fch + 8 * (x4 >> 1)); // p block 0; per pb: ^ (64 pb) bytes
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int pb = 0; pb < PB; ++pb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) accO[mb][pb][r] = 0.f;
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb)
+#pragma unroll
+            for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+                for (int qp = 0; qp < 2; ++qp) {
+                    const lds_u8 *src = smem + (f_off ^ (unsigned)(64 * pb)) + (32 * hb + 8 * qp) * RBF;
+                    i16x4 lo = lds_read_tr(src);
+                    i16x4 hi = lds_read_tr(src + 4 * RBF);
+                    const v8 fop = __builtin_bit_cast(v8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) accO[mb][pb] = M_::run(fop, eop[mb][hb][qp], accO[mb][pb]);
+                }
+        if constexpr (NS > 1) { // from here on the partial products take the place of the partial E
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int hb = 0; hb < HB; ++hb) accE[mb][hb] = accO[mb][hb];
+        }
+    }
+
     // ---- combine the ns partial results of a row-group -----------------------------------
     // The MB*HB accumulator blocks (32 rows x 32 columns of E each) of a row-group are dealt
     // out to its ns waves in contiguous runs of BPW; every wave parks the blocks it does not
@@ -820,6 +877,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
                         // a wave that saw no column has m = -inf, l = 0 and a zero accumulator
                         f[w] = (mw[w] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((mw[w] - m_all) * c1);
                         l_all += f[w] * lw[w];
+                        if (CH3) f[w] *= lw[w]; // the partial products were formed from E_w / l_w
                     }
                     l_run[mb] = l_all;
                 }
@@ -849,48 +907,6 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     float inv[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) inv[mb] = SOFTMAX ? 1.0f / l_run[mb] : 1.0f;
-    constexpr int PB = CH3 ? PD / 32 : 1;
-    f32x16 accO[MB][PB]; // the product E.F of the three-GEMM chain (unused otherwise)
-    if constexpr (CH3) {
-        // ---- third GEMM: G^T[p][m] = sum_h F^T[p][h] E^T[h][m] ----------------------------------
-        // The accumulator of GEMM 2 holds, in lane (c,g), E[row c][32hb + 16g + r]; its registers
-        // 8qp .. 8qp+7, normalised and rounded to 16 bit, are the second MFMA operand for the 16
-        // contraction indices h = 32hb + 16g' + 8qp + e (g' the half-wave, e = 0..7).  The first
-        // operand is read from the F tile with the transposing read, rows h in that order,
-        // columns p mapped as the h of GEMM 2 so that a lane again ends with 16 consecutive p.
-        v8 eop[MB][HB][2];
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-            for (int hb = 0; hb < HB; ++hb)
-#pragma unroll
-                for (int qp = 0; qp < 2; ++qp)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) eop[mb][hb][qp][e] = (T)(accE[mb][hb][8 * qp + e] * inv[mb]);
-        const int x4 = i16 & 3;
-        const int frow = 16 * g + (i16 >> 2); // + 32 hb + 8 qp; upper four contraction indices: + 4 rows
-        const int fch = (u16 + 2 * (x4 & 1)) ^ swz_tr(RBF, frow);
-        const unsigned f_off = (unsigned)(F_LDS + frow * RBF + 16 * fch + 8 * (x4 >> 1)); // p block 0; per pb: ^ (64 pb) bytes
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-            for (int pb = 0; pb < PB; ++pb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) accO[mb][pb][r] = 0.f;
-#pragma unroll
-        for (int pb = 0; pb < PB; ++pb)
-#pragma unroll
-            for (int hb = 0; hb < HB; ++hb)
-#pragma unroll
-                for (int qp = 0; qp < 2; ++qp) {
-                    const lds_u8 *src = smem + (f_off ^ (unsigned)(64 * pb)) + (32 * hb + 8 * qp) * RBF;
-                    i16x4 lo = lds_read_tr(src);
-                    i16x4 hi = lds_read_tr(src + 4 * RBF);
-                    const v8 fop = __builtin_bit_cast(v8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) accO[mb][pb] = M_::run(fop, eop[mb][hb][qp], accO[mb][pb]);
-                }
-    }
 
     // ---- S_E: output tile -> global ---------------------------------------------------------
     // Lane (c,g) holds X[row c][32hb + 16g + 0..15] of the blocks its wave owns (X = E, or the
@@ -912,7 +928,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         lds_u8 *es = smem + combine_bytes(LDX, MB, RG, NS) + wave * estage_wave_bytes(LDX, MB, NS);
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-            const float sc = CH3 ? 1.0f : inv[mb];
+            const float sc = inv[mb]; // (the product of a single wave per row set is final: not scaled)
 #pragma unroll
             for (int hb = 0; hb < HBX; ++hb) {
                 const int blk = mb * HBX + hb;
@@ -922,7 +938,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
                     v8 lo, hi;
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        if constexpr (CH3) {
+                        if constexpr (CH3 && NS == 1) {
                             lo[e] = (T)accO[mb][hb][e];
                             hi[e] = (T)accO[mb][hb][8 + e];
                         } else {
@@ -958,7 +974,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
 template <int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool KSPLIT, int PD>
 constexpr int kernel_lds_bytes() {
     constexpr int S = ring_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX, KSPLIT);
-    if constexpr (PD > 0) return chain3_lds_bytes(KD, LD, PD, MB, RG, NJ, S);
+    if constexpr (PD > 0) return chain3_lds_bytes(KD, LD, PD, MB, RG, NS, NJ, S);
     else return total_lds_bytes(KD, LD, MB, RG, NS, NJ, S, KSPLIT);
 }
 
@@ -989,7 +1005,7 @@ int launch_chain(const KParams &p, void *stream) {
 template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool BKC, bool KSPLIT = false, int PD = 0>
 constexpr LaunchFn launcher_or_null() {
     if constexpr (kernel_lds_bytes<KD, LD, MB, RG, NS, NJ, SOFTMAX, KSPLIT, PD>() <= kLdsBytesPerBlock &&
-                  combine_runs_ok(LD, MB, NS) && (PD == 0 || NS == 1))
+                  combine_runs_ok(LD, MB, NS) && (PD == 0 || NS == 1 || PD == LD))
         return &launch_chain<T, KD, LD, MB, RG, NS, NJ, SOFTMAX, BKC, KSPLIT, PD>;
     else
         return nullptr;

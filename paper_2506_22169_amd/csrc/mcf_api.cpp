@@ -82,8 +82,8 @@ static const Variant *find_variant3(int dtype, int64_t K, int64_t L, int64_t P, 
 }
 
 // Tile choice for the three-GEMM chain: the arrangement (among those built for it) whose
-// two-GEMM part the model ranks best (ties: the larger nj, as in the two-GEMM ranking); the
-// third GEMM adds the same work to each of them.
+// two-GEMM part the model ranks best (ties broken as for the two-GEMM chain); the third GEMM
+// adds the same work to each of them.
 static int pick3(const mcf_problem *p, int softmax, int b_kcontig, int64_t P, mcf_tiles *out) {
     int n = 0;
     const Variant *v = variants3(&n);
@@ -97,7 +97,8 @@ static int pick3(const mcf_problem *p, int softmax, int b_kcontig, int64_t P, mc
         t.mb = v[i].mb; t.rg = v[i].rg; t.ns = v[i].ns; t.nj = v[i].nj;
         const int st = mcf_eval_tiles(p, softmax, &t);
         if (st != MCF_OK && st != MCF_EINVAL) continue;
-        if (!have || t.t_est_s < out->t_est_s || (t.t_est_s == out->t_est_s && t.nj > out->nj)) { *out = t; have = true; }
+        t.lds_bytes = lds_bytes_for(&v[i]); // with the F tile
+        if (!have || better(t, *out)) { *out = t; have = true; }
     }
     return have ? MCF_OK : MCF_EUNSUPPORTED;
 }
@@ -164,7 +165,7 @@ static int run(const mcf_problem *p_in, int softmax, float scale, const void *A,
         mcf_tiles any;
         return pick3(p, softmax, lay.b_kcontig, P, &any) == MCF_OK ? MCF_EINVAL : MCF_EUNSUPPORTED;
     }
-    if (!ch3 && lds_bytes_for(v) > kLdsBytesPerBlock)
+    if (lds_bytes_for(v) > kLdsBytesPerBlock)
         return MCF_EINVAL; // more LDS than a compute unit has
 
     const int64_t tm = 32ll * v->mb * v->rg;

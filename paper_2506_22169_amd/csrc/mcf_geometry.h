@@ -80,15 +80,16 @@ constexpr int total_lds_bytes(int K, int L, int mb, int rg, int ns, int nj, int 
     const int c = combine_bytes(L, mb, rg, ns) + estage_bytes(L, mb, rg, ns);
     return s > c ? s : c;
 }
-// Three-GEMM chain (E . F with F[L x P] after the loop; ns = 1): the F tile sits behind
-// everything else for the whole life of the block; the output tile is staged like E.
+// Three-GEMM chain (E . F with F[L x P] after the loop): the F tile sits behind everything else
+// for the whole life of the block; the output tile is combined and staged like E.
 constexpr int chain3_f_bytes(int L, int P) { return L * pitch_elems(P) * 2; }
-constexpr int chain3_f_offset(int K, int L, int P, int mb, int rg, int nj, int stages) {
-    const int t = total_lds_bytes(K, L, mb, rg, 1, nj, stages), e = estage_bytes(P, mb, rg, 1);
+constexpr int chain3_f_offset(int K, int L, int P, int mb, int rg, int ns, int nj, int stages) {
+    const int t = total_lds_bytes(K, L, mb, rg, ns, nj, stages);
+    const int e = combine_bytes(P, mb, rg, ns) + estage_bytes(P, mb, rg, ns);
     return ((t > e ? t : e) + 1023) / 1024 * 1024;
 }
-constexpr int chain3_lds_bytes(int K, int L, int P, int mb, int rg, int nj, int stages) {
-    return chain3_f_offset(K, L, P, mb, rg, nj, stages) + chain3_f_bytes(L, P);
+constexpr int chain3_lds_bytes(int K, int L, int P, int mb, int rg, int ns, int nj, int stages) {
+    return chain3_f_offset(K, L, P, mb, rg, ns, nj, stages) + chain3_f_bytes(L, P);
 }
 // Largest ring depth (2..4) that keeps a block within `budget` bytes of LDS.
 constexpr int pick_stages(int K, int L, int mb, int rg, int ns, int nj, int budget, bool ksplit = false) {

@@ -42,14 +42,23 @@
     X(2, 2, 2, 1)            \
     X(2, 1, 4, 1)
 
-// Arrangements built for the three-GEMM chain (one wave per row set: ns = 1).
+// Arrangements built for the three-GEMM chain.
 #define MCF_CHAIN3_SHAPES(X) \
     X(1, 4, 1, 1)            \
     X(1, 4, 1, 2)            \
     X(1, 8, 1, 1)            \
     X(1, 8, 1, 2)            \
     X(2, 4, 1, 1)            \
-    X(2, 4, 1, 2)
+    X(2, 4, 1, 2)            \
+    X(1, 1, 4, 1)            \
+    X(1, 2, 2, 1)            \
+    X(1, 2, 2, 2)            \
+    X(1, 4, 2, 1)            \
+    X(1, 4, 2, 2)            \
+    X(2, 2, 2, 2)            \
+    X(2, 2, 4, 1)            \
+    X(2, 4, 2, 1)            \
+    X(2, 4, 2, 2)
 
 namespace mcf {
 

@@ -72,6 +72,7 @@ int decode_layout(const mcf_problem *p, Layout *out); // MCF_OK or an error stat
 // Ring depth and LDS bytes of a variant; register estimate per lane.
 int stages_for(const Variant *v);
 int lds_bytes_for(const Variant *v);
+bool better(const mcf_tiles &a, const mcf_tiles &b); // the picker's order: estimate, then the tie-breaks
 int vgpr_estimate(int K, int L, int mb, int rg, int ns, int nj, int softmax, int ksplit);
 
 // Feasible candidates for a problem, with their model terms, in registry order (the set

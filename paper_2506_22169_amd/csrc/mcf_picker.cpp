@@ -38,6 +38,7 @@ int stages_for(const Variant *v) {
     return ring_stages(v->K, v->L, v->mb, v->rg, v->ns, v->nj, v->softmax != 0, v->ksplit != 0);
 }
 int lds_bytes_for(const Variant *v) {
+    if (v->P > 0) return chain3_lds_bytes(v->K, v->L, v->P, v->mb, v->rg, v->ns, v->nj, stages_for(v));
     return total_lds_bytes(v->K, v->L, v->mb, v->rg, v->ns, v->nj, stages_for(v), v->ksplit != 0);
 }
 
@@ -114,7 +115,7 @@ static bool feasible(const mcf_tiles &t) {
 // does not see how the waves of a block are arranged) more waves per block, then a block
 // whose LDS leaves room for a second one on the compute unit, then fewer waves across n (less
 // to combine), then more column slices per wave, then fewer rows per wave.
-static bool better(const mcf_tiles &a, const mcf_tiles &b) {
+bool better(const mcf_tiles &a, const mcf_tiles &b) {
     if (a.t_est_s != b.t_est_s) return a.t_est_s < b.t_est_s;
     if (a.tl != b.tl) return a.tl > b.tl;
     if (a.waves != b.waves) return a.waves > b.waves;

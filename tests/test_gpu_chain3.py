@@ -89,8 +89,8 @@ def test_chain3_errors():
     with pytest.raises(mcf.McfError) as e:                       # P not built
         mcf.gemm_chain3(A, A, A, torch.zeros((1, 64, 32), dtype=torch.float16, device="cuda"))
     assert e.value.status == 2
-    with pytest.raises(mcf.McfError) as e:                       # an arrangement with ns > 1
-        mcf.gemm_chain3(A, A, A, F, tiles=(1, 4, 2, 1))
+    with pytest.raises(mcf.McfError) as e:                       # an arrangement that is not built for three GEMMs
+        mcf.gemm_chain3(A, A, A, F, tiles=(4, 2, 2, 1))
     assert e.value.status == 1
     with pytest.raises(mcf.McfError) as e:                       # output aliases F
         mcf.gemm_chain3(A, A, A, F, out=F)
