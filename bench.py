@@ -13,7 +13,9 @@ Python call overhead; --eager times plain calls instead.
 
 Prints ONE JSON line: the BASELINE metric (effective HBM GB/s on compulsory bytes) with a
 `roofline` object for the chain kernel and a `cpu_baseline` object (the fp64 oracle timed on
-this host's cores).
+this host's cores).  The metric is quoted per configuration: a default run also times the other
+four configurations after the timed region (one child process each, same protocol, 1000 steps;
+the long attention 40) and reports them under `per_config`; `value` stays cfg2's.
 """
 import argparse
 import json
@@ -46,6 +48,10 @@ def parse_args():
     ap.add_argument("--eager", action="store_true", help="time plain calls instead of a HIP graph replay")
     ap.add_argument("--warm", action="store_true", help="reuse one buffer set (cache-resident operands)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="with the default workload (and the CPU baseline leg on) the other four configurations are timed "
+                         "as well (child processes, after the timed region) and reported under 'per_config'; this "
+                         "switches that off")
     ap.add_argument("--copy-ref", type=int, default=0, metavar="MiB",
                     help="after the timed region also run one plain device copy of this many MiB (the "
                          "known-size kernel that calibrates the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -272,6 +278,27 @@ def main():
         "cpu_baseline": cpu_baseline,
         "parity": parity,
     }
+    # ---- the metric is quoted per configuration: time the other four as well (context; `value` is cfg2's) ----
+    if (args.workload == "cfg2" and not args.no_per_config and not args.no_cpu_baseline
+            and not (args.chain3 or args.tune or args.tiles or args.warm or args.eager)):
+        import subprocess
+        per = {"cfg2": {"us_per_launch": t_kernel * 1e6, "gbs": gbs, "tflops": tflops, "bound": bound, "frac": achieved / peak,
+                        "tiles": [picked.mb, picked.rg, picked.ns, picked.nj, picked.tl]}}
+        del sets
+        torch.cuda.empty_cache()
+        for name in ("cfg1", "cfg3", "cfg4", "cfg5"):
+            steps = 40 if name == "cfg5" else 1000
+            try:
+                r = subprocess.run([sys.executable, os.path.abspath(__file__), "--workload", name, "--steps", str(steps), "--warmup", "50",
+                                    "--no-cpu-baseline", "--no-per-config"], capture_output=True, text=True, timeout=240)
+                d = json.loads(r.stdout.strip().splitlines()[-1])
+                t = d["config"]["tiles"]
+                per[name] = {"us_per_launch": d["us_per_launch_events"], "gbs": d["value"], "tflops": d["tflops"],
+                             "bound": d["roofline"]["bound"], "frac": d["roofline"]["frac"],
+                             "tiles": [t["mb"], t["rg"], t["ns"], t["nj"], t["tl"]]}
+            except Exception as e:      # context only: never fail the benchmark line over it
+                per[name] = {"error": str(e)[:200]}
+        out["per_config"] = per
     print(json.dumps(out))
     return 0
 
