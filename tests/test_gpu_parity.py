@@ -1,5 +1,7 @@
 """Parity of the HIP path (through the C ABI) with the fp64 oracle, element by element, on
 seeded inputs that span several tiles and ragged tails.  Needs an MI355X."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -194,11 +196,13 @@ def test_random_shapes_strides_and_tiles():
     non-packed row and batch strides on every operand and on the output, and a random built
     wave arrangement, each compared with the oracle element by element; the padding around a
     strided output must come back untouched."""
-    rng = np.random.default_rng(20250622)
+    # MCF_SWEEP_SEED / MCF_SWEEP_CASES: a longer or different sweep for a one-off run
+    rng = np.random.default_rng(int(os.environ.get("MCF_SWEEP_SEED", "20250622")))
+    n_cases = int(os.environ.get("MCF_SWEEP_CASES", "72"))
     groups = [(32, 32), (64, 64), (128, 128), (64, 128), (128, 64), (64, 256), (256, 256), (256, 128), (640, 64), (80, 80)]
     sizes = [1, 2, 7, 31, 32, 33, 64, 100, 129, 255, 300, 517]
     worst = 0.0
-    for case in range(72):
+    for case in range(n_cases):
         K, L = groups[rng.integers(len(groups))]
         dtype = ("f16", "bf16")[rng.integers(2)]
         softmax = bool(rng.integers(2))
@@ -232,7 +236,8 @@ def test_random_shapes_strides_and_tiles():
         _, D = strided(D0, N, L, pad[2], gap[2])
         Ebig, E = strided(torch.zeros((b, M, L), dtype=tdt, device="cuda"), M, L, pad[3], gap[3], fill=5.0)
         prob = mcf.binding._problem_from_tensors(A, B, D, E)
-        shapes = [s for s in mcf.list_variants(prob, softmax)]
+        shapes = [(t.mb, t.rg, t.ns, t.nj, t.tl) for t in mcf.list_candidates(prob, softmax)]   # all T_L options
+        shapes += [s for s in mcf.list_variants(prob, softmax)]           # and arrangements Rule 3 / the LDS rule would drop
         tiles = shapes[rng.integers(len(shapes))] if case % 4 else None   # every fourth case: the picker
         print(f"case {case}: b={b} M={M} K={K} N={N} L={L} {dtype} softmax={softmax} nk={nk} pad={pad} gap={gap} "
               f"tiles={tiles}", flush=True)
