@@ -95,3 +95,43 @@ def test_chain3_errors():
     with pytest.raises(mcf.McfError) as e:                       # output aliases F
         mcf.gemm_chain3(A, A, A, F, out=F)
     assert e.value.status == 1
+
+
+def test_chain3_random_sweep():
+    """Seeded sweep over group, dtype, chain kind, B layout, sizes, row pitches of F and G and
+    the built arrangements (MCF_SWEEP_SEED / MCF_SWEEP_CASES: a longer or different one-off run)."""
+    import os
+    rng = np.random.default_rng(int(os.environ.get("MCF_SWEEP_SEED", "31415")))
+    n_cases = int(os.environ.get("MCF_SWEEP_CASES", "48"))
+    sizes = [1, 2, 7, 31, 32, 33, 64, 100, 129, 255, 300, 517]
+    worst = 0.0
+    for case in range(n_cases):
+        K = L = P = (64, 128)[rng.integers(2)]
+        dtype = ("f16", "bf16")[rng.integers(2)]
+        softmax = bool(rng.integers(2))
+        nk = bool(rng.integers(2))
+        b = int(rng.integers(1, 4))
+        M = int(sizes[rng.integers(len(sizes))])
+        N = int(sizes[rng.integers(len(sizes))])
+        if not nk:
+            N = max(8, (N + 7) // 8 * 8)
+        padf, padg = int(8 * rng.integers(0, 3)), int(8 * rng.integers(0, 3))
+        w, x, f_bits, F64 = _inputs(b, M, K, N, L, P, dtype, softmax, seed=9500 + case)
+        A, B, D = device_inputs(w, x)                       # B is [b,K,N]: N-contiguous for plain, K-contiguous for softmax
+        if nk != softmax:
+            B = B.transpose(1, 2).contiguous().transpose(1, 2) if nk else B.contiguous()
+        tdt = torch.float16 if dtype == "f16" else torch.bfloat16
+        Fbig = torch.zeros((b, L, P + padf), dtype=tdt, device="cuda")
+        Fbig[:, :, :P] = to_device(f_bits, dtype)
+        Gbig = torch.full((b, M, P + padg), 5.0, dtype=tdt, device="cuda")
+        prob = mcf.binding._problem_from_tensors(A, B, D, mcf.binding._MetaLike(A, D))
+        shapes = mcf.list_variants3(prob, P, softmax)
+        tiles = shapes[rng.integers(len(shapes))] if case % 4 else None
+        print(f"case {case}: b={b} M={M} K={K} N={N} {dtype} softmax={softmax} nk={nk} padf={padf} padg={padg} tiles={tiles}",
+              flush=True)
+        mcf.gemm_chain3(A, B, D, Fbig[:, :, :P], scale=w.scale if softmax else None, out=Gbig[:, :, :P], tiles=tiles)
+        torch.cuda.synchronize()
+        ref = oracle.chain3(x["A"], x["B"], x["D"], F64, softmax=softmax, scale=w.scale)
+        worst = max(worst, _check(to_host64(Gbig[:, :, :P], dtype), ref, f"case {case}"))
+        assert bool((Gbig[:, :, P:] == 5.0).all()), f"case {case}: wrote outside the output view"
+    print(f"worst max|err|/max|oracle| = {worst:.3e}", flush=True)
