@@ -204,9 +204,16 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     }
     // With T_L < L (h_tiles > 1) the LD columns [ht * LD, ht * LD + LD) of D and E are a block
     // of their own; the h tiles of one (batch, m-tile) are neighbours, so they share A and B in L2.
-    const int bm = h_tiles == 1 ? logical : logical / h_tiles;
+    const unsigned h_magic = p.h_magic, m_magic = p.m_magic;
+    const int h_shift = p.h_shift, m_shift = p.m_shift;
+    // one scalar load at the very top for all of them (left alone, the compiler fetches them
+    // piecemeal, each piece with a wait of its own before the first load can be issued)
+    asm volatile("" ::"s"(n_blocks), "s"(m_tiles), "s"(h_tiles), "s"(h_magic), "s"(m_magic), "s"(h_shift), "s"(m_shift), "s"(M));
+    const int bm_q = (int)(__umulhi((unsigned)logical, h_magic) >> h_shift);
+    const int bm = h_magic ? bm_q : logical;   // logical / h_tiles
     const int ht = logical - bm * h_tiles;
-    const int batch = bm / m_tiles;
+    const int batch_q = (int)(__umulhi((unsigned)bm, m_magic) >> m_shift);
+    const int batch = m_magic ? batch_q : bm;  // bm / m_tiles
     const int mt = bm - batch * m_tiles;
     const int mrow0 = mt * TM; // first row of the block
 
@@ -246,11 +253,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             return (unsigned)(row * sd_r * 2 + ch * 16);
         }
     };
-    unsigned voff[P];
-    if constexpr (!KSPLIT) {
-#pragma unroll
-        for (int u = 0; u < P; ++u) voff[u] = bd_offset(u, 0, false);
-    }
+    unsigned voff[P]; // filled after the A tile has been requested: the first load leaves as early as possible
 
     const int n_iters = (N + TN - 1) / TN;
     const int n_full = N / TN; // tiles [0, n_full) are complete, tile n_full (if any) is ragged
@@ -394,6 +397,8 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             if (mrow0 + row >= M) row = M - 1 - mrow0; // rows past M: any valid row, never stored
             dma16_once(dst0 + (jj - wave) * 1024, (unsigned)(row * sa_r * 2 + ch * 16), abase);
         }
+#pragma unroll
+        for (int u = 0; u < P; ++u) voff[u] = bd_offset(u, 0, false);
     }
     const int n_items = KSPLIT ? n_iters * (KC + 1) : n_iters; // ring items of the whole block
     const int n_pre = n_items < S - 1 ? n_items : S - 1;

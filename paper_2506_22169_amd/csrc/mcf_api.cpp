@@ -184,6 +184,8 @@ static int run(const mcf_problem *p_in, int softmax, float scale, const void *A,
     k.m_tiles = (int32_t)m_tiles;
     k.h_tiles = (int32_t)h_tiles;
     k.n_blocks = (int32_t)(p->batch * m_tiles * h_tiles);
+    division_magic((uint32_t)m_tiles, &k.m_magic, &k.m_shift);
+    division_magic((uint32_t)h_tiles, &k.h_magic, &k.h_shift);
     k.c1 = 1.0f; k.a_mode = 0;
     k.k_chunks = (int32_t)(p->K / v->K);
     k.F = F; k.sf_b = sf[0]; k.sf_r = sf[1];

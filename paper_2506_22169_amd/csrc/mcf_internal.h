@@ -21,22 +21,37 @@ constexpr int kVgprBudget = 512;              // arch + accumulation VGPRs per l
 
 // Kernel arguments (device pointers, element strides).
 struct KParams {
+    // what a block needs first (its place in the problem): together at the start, one scalar load
+    int32_t n_blocks;   // batch * m_tiles * h_tiles
+    int32_t m_tiles;    // ceil(M / T_M)
+    int32_t h_tiles;    // L / T_L: column tiles of E, each a block of its own (1 when T_L = L)
+    // floor(n / m_tiles) = umulhi(n, m_magic) >> m_shift for 0 <= n < 2^31 (m_magic = 0: m_tiles = 1);
+    // the same for h_tiles.  Saves the blocks an integer division each before their first load.
+    uint32_t m_magic, h_magic;
+    int32_t m_shift, h_shift;
+    int32_t M, N;
+    int32_t a_mode;     // 0: A as is, 1: -A (negative scale), 2: A := 0 (scale == 0)
+    int32_t k_chunks;   // kernels with a k loop: K / T_K (otherwise unused)
+    float c1;           // |scale| * log2(e) (softmax only)
     const void *A, *B, *D;
     void *E;
     int64_t sa_b, sa_r; // A: batch / row stride (col stride 1)
     int64_t sb_b, sb_r; // B: batch stride / stride of the non-contiguous index
     int64_t sd_b, sd_r; // D: batch / row stride
     int64_t se_b, se_r; // E: batch / row stride
-    int32_t M, N;
-    int32_t m_tiles;    // ceil(M / T_M)
-    int32_t h_tiles;    // L / T_L: column tiles of E, each a block of its own (1 when T_L = L)
-    int32_t n_blocks;   // batch * m_tiles * h_tiles
-    float c1;           // |scale| * log2(e) (softmax only)
-    int32_t a_mode;     // 0: A as is, 1: -A (negative scale), 2: A := 0 (scale == 0)
-    int32_t k_chunks;   // kernels with a k loop: K / T_K (otherwise unused)
     const void *F;      // three-GEMM chain: F[b, L, P] (col stride 1); E is then the output [b, M, P]
     int64_t sf_b, sf_r; // F: batch / row stride
 };
+
+// magic, shift with floor(n / d) = umulhi(n, magic) >> shift for every 0 <= n < 2^31 (d >= 1;
+// magic = 0 stands for d = 1): magic = ceil(2^(31+s) / d), s = ceil(log2 d), shift = s - 1.
+inline void division_magic(uint32_t d, uint32_t *magic, int32_t *shift) {
+    if (d <= 1) { *magic = 0; *shift = 0; return; }
+    int s = 0;
+    while ((1ull << s) < d) ++s;
+    *magic = (uint32_t)(((1ull << (31 + s)) + d - 1) / d);
+    *shift = s - 1;
+}
 
 typedef int (*LaunchFn)(const KParams &p, void *stream); // returns hipError_t as int
 
