@@ -397,8 +397,18 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             if (mrow0 + row >= M) row = M - 1 - mrow0; // rows past M: any valid row, never stored
             dma16_once(dst0 + (jj - wave) * 1024, (unsigned)(row * sa_r * 2 + ch * 16), abase);
         }
+        // Wave-load u of a wave covers rows 64 W / (chunks per row) further down than wave-load
+        // u - 1 of the same tile, at the same chunk and (the step being a multiple of the
+        // swizzle period) the same swizzle: one addition instead of the whole computation.
+        constexpr bool INC = CB % W == 0 && CT % W == 0 && !KPAD && !LPAD && (64 * W) % (RBB / 16) == 0 &&
+                             (64 * W) % (RBD / 16) == 0 && ((64 * W) / (RBB / 16)) % 16 == 0 && ((64 * W) / (RBD / 16)) % 16 == 0;
 #pragma unroll
-        for (int u = 0; u < P; ++u) voff[u] = bd_offset(u, 0, false);
+        for (int u = 0; u < P; ++u) {
+            if (INC && u > 0 && (u * W < CB) == ((u - 1) * W < CB))
+                voff[u] = voff[u - 1] + (unsigned)(u * W < CB ? ((64 * W) / (RBB / 16)) * sb_r * 2 : ((64 * W) / (RBD / 16)) * sd_r * 2);
+            else
+                voff[u] = bd_offset(u, 0, false);
+        }
     }
     const int n_items = KSPLIT ? n_iters * (KC + 1) : n_iters; // ring items of the whole block
     const int n_pre = n_items < S - 1 ? n_items : S - 1;
