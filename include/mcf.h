@@ -48,9 +48,10 @@ typedef enum {
  *   Every non-unit row stride and every batch stride is a multiple of 8 elements; for
  *   N-contiguous B, N itself is a multiple of 8.  Base pointers are 16-byte aligned.
  * Supported here: (K, L) in {(32,32), (64,64), (128,128), (64,128), (128,64), (64,256),
- * (256,256), (80,80)} with the whole K extent on chip (T_K = K), and every other K >= 256 that is a
+ * (256,256), (80,80), (96,96), (160,160), (192,192)} with the whole K extent on chip (T_K = K),
+ * and every other K >= 256 that is a
  * multiple of 128 with L in {64, 128, 256} through kernels with a k loop inside the block
- * (T_K = 128); T_L = L always.  Any batch, M >= 0, N >= 0 (N >= 1 with softmax).  Other
+ * (T_K = 128).  Any batch, M >= 0, N >= 0 (N >= 1 with softmax).  Other
  * (K, L) give MCF_EUNSUPPORTED.
  * in_dtype is the type of A, B, D; out_dtype that of E and must equal in_dtype.
  * Both GEMMs accumulate in fp32; C (or P) is rounded once to in_dtype between them.

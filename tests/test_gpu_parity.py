@@ -21,7 +21,7 @@ pytestmark = pytest.mark.gpu
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 @pytest.mark.parametrize("KL", [(32, 32), (64, 64), (128, 128), (64, 128), (128, 64), (64, 256), (256, 256),
                                 (256, 64), (384, 128), (512, 256),    # these three: k loop inside the block
-                                (80, 80)])                            # rows padded to a power-of-two pitch in LDS
+                                (80, 80), (96, 96), (160, 160), (192, 192)])   # rows padded to a power-of-two pitch in LDS
 def test_every_variant_small_ragged(KL, dtype, softmax):
     """Every built wave arrangement on a shape with a ragged m tail and a ragged n tail that
     spans several tiles of the largest variant (tm up to 256, tn up to 256)."""
@@ -199,7 +199,8 @@ def test_random_shapes_strides_and_tiles():
     # MCF_SWEEP_SEED / MCF_SWEEP_CASES: a longer or different sweep for a one-off run
     rng = np.random.default_rng(int(os.environ.get("MCF_SWEEP_SEED", "20250622")))
     n_cases = int(os.environ.get("MCF_SWEEP_CASES", "72"))
-    groups = [(32, 32), (64, 64), (128, 128), (64, 128), (128, 64), (64, 256), (256, 256), (256, 128), (640, 64), (80, 80)]
+    groups = [(32, 32), (64, 64), (128, 128), (64, 128), (128, 64), (64, 256), (256, 256), (256, 128), (640, 64), (80, 80),
+              (96, 96), (160, 160), (192, 192)]
     sizes = [1, 2, 7, 31, 32, 33, 64, 100, 129, 255, 300, 517]
     worst = 0.0
     for case in range(n_cases):
