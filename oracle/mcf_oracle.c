@@ -157,8 +157,8 @@ void mcf_oracle_intermediate_row(int64_t batch, int64_t M, int64_t K, int64_t N,
 }
 
 /*
- * Chain of three GEMMs (Sec. III-A: the analysis "extends to scenarios with more
- * compute-intensive operators"): G[b,i,p] = sum_h E[b,i,h] * F[b,h,p] with E as above (the
+ * Chain of three GEMMs (Sec. III-A: the tiling analysis carries over to longer chains of
+ * compute-intensive operators): G[b,i,p] = sum_h E[b,i,h] * F[b,h,p] with E as above (the
  * softmax, if any, sits between the first two GEMMs).  One row of E is materialised per (b,i)
  * and nothing is rounded.  G packed [batch, M, P].  Returns the number of threads used.
  */

@@ -74,8 +74,9 @@ def neighbours(space, i, loop):
 
 
 def heuristic_search(space, estimates, measure, N, n, epsilon, seed, max_generations=16, rng=None):
-    """Alg. 1.  Returns a dict: best (candidate index), best_t, converged, generations, and
-    log = [(generation, candidate index, estimate, measured time)] in measurement order.
+    """Alg. 1.  Returns a dict: best (candidate index), best_t, converged, generations,
+    log = [(generation, candidate index, estimate, measured time)] in measurement order, and
+    populations = the population of every generation as it was drawn (before the sort).
     `rng` (an object with next() and below(n)) replaces the seeded generator in tests."""
     assert len(space) == len(estimates) and len(space) > 0
     rng = rng if rng is not None else Uniforms(seed)
@@ -91,8 +92,10 @@ def heuristic_search(space, estimates, measure, N, n, epsilon, seed, max_generat
             population.append(rng.below(len(space)))
     best_t, best_cand = 1e9, None
     measured, log = {}, []
+    populations = []
     generation, converged = 0, False
     while True:
+        populations.append(list(population))
         estimated_ts = {c: estimates[c] for c in population}           # estimatePerformance
         population = sorted(population, key=lambda c: (estimated_ts[c], c))
         topk_cands = []
@@ -136,4 +139,5 @@ def heuristic_search(space, estimates, measure, N, n, epsilon, seed, max_generat
             options = neighbours(space, parent, loop)
             nxt.append(options[min(int(u * len(options)), len(options) - 1)] if options else parent)
         population = nxt
-    return {"best": best_cand, "best_t": best_t, "converged": converged, "generations": generation, "log": log}
+    return {"best": best_cand, "best_t": best_t, "converged": converged, "generations": generation, "log": log,
+            "populations": populations}

@@ -96,3 +96,30 @@ def test_eq2_to_5_hand_evaluated():
     # split bandwidths: re-read bytes charged at the faster level
     s = pm.estimate("mhnk", dims, tiles, 1, 2, W=1e12, P=1e14, n_units=100, W_reread=4e12)
     assert s["t_mem"] == pytest.approx(262144 / 1e12 + (1179648 - 262144) / 4e12, rel=1e-15)
+
+
+def test_block_loops_keep_their_statements():
+    """Sec. III-B removes loops of extent 1 and re-hoists; read here so that no statement leaves
+    the loops bound to the block index (m, h, batch), because blocks share no on-chip memory.
+    Hand-evaluated: dims M=256 N=128 K=32 H=64, tiles 64/128/32/32, batch 3, 2-byte elements:
+    extents m=4, n=1, k=1, h=2 -> 24 blocks, each loading its A tile (64x32), the whole B
+    (32x128), its D tile (128x32), computing C (64x128 over K=32) and E (64x32 over N=128) and
+    storing its E tile (64x32).  (Without the reading L_B would run once, L_A and C_C 4 times.)"""
+    dims = {"m": 256, "n": 128, "k": 32, "h": 64}
+    tiles = {"m": 64, "n": 128, "k": 32, "h": 32}
+    r = pm.estimate("mhnk", dims, tiles, batch=3, elem_bytes=2, W=1e12, P=1e14, n_units=100)
+    assert r["n_block"] == 24
+    assert r["mem_bytes"] == {"L_A": 24 * 64 * 32 * 2, "L_B": 24 * 32 * 128 * 2, "L_D": 24 * 128 * 32 * 2,
+                              "S_E": 24 * 64 * 32 * 2}
+    assert r["mem_bytes"] == {"L_A": 98304, "L_B": 196608, "L_D": 196608, "S_E": 98304}
+    assert r["model_bytes"] == 589824 and r["compulsory_bytes"] == 221184
+    assert r["flops"] == 24 * (2 * 64 * 128 * 32 + 2 * 64 * 128 * 32) == 25165824
+    assert r["alpha"] == pytest.approx(124 / 24, rel=1e-15)
+    assert r["t_estm"] == pytest.approx(4.34765824e-6, rel=1e-12)
+    # the same through trips(): the block loops hold L_B although k and n are dead
+    ext = pm.extents_of(dims, tiles)
+    assert pm.trips("mhnk", "L_B", ext, block_loops="mh") == 8 and pm.trips("mhnk", "L_B", ext) == 1
+    assert pm.trips("mhnk", "L_A", ext, block_loops="mh") == 8 and pm.trips("mhnk", "L_A", ext) == 4
+    # T_N = N, T_K = K with one h tile (the case of the five evaluated workloads when N fits a tile)
+    one_h = pm.estimate("mhnk", dims, dict(tiles, h=64), batch=3, elem_bytes=2, W=1e12, P=1e14, n_units=100)
+    assert one_h["mem_bytes"]["L_B"] == 12 * 32 * 128 * 2 and one_h["mem_bytes"]["L_D"] == 12 * 128 * 64 * 2

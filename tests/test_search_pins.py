@@ -80,6 +80,58 @@ def test_hand_traced_run():
     assert rng.k == len(us)      # every scripted number was consumed, none more
 
 
+def test_hand_traced_parent_weights_and_first_population():
+    """A second run traced by hand whose scripted numbers separate the readings that the first
+    one cannot: the first population is drawn without repetition (Alg. 1, first statement, as
+    read here), and parents are drawn with probability proportional to 1 / estimate (Sec. IV-B,
+    mutate paragraph), not to the estimate.  Same space as above: 0:(m1,n1) 1:(m2,n1) 2:(m1,n2)
+    3:(m2,n2), estimates 4, 2, 3, 1; measured 5, 1.5, 3, 1.2.  N = 3, n = 2, three generations.
+
+    gen 0: draws .1,.1,.1.  Without repetition: position 0 takes perm[0 + int(.1*4)] = 0,
+           position 1 takes perm[1 + int(.1*3)] = 1, position 2 takes perm[2 + int(.1*2)] = 2:
+           population [0,1,2]  (with repetition it would be [0,0,0]).
+           by estimate [1,2,0]; measure 1 (1.5) and 2 (3.0); top1 = 1; best = (1, 1.5).
+           weights 1/2,1/3,1/4, cumulative .5, .8333, 1.0833 (total 1.0833):
+             .3*1.0833=.325   -> parent 1 (weights 2,3,4 would give 2.7 -> parent 2);
+                                 loop .7 -> n, only neighbour 3                       -> 3
+             .6*1.0833=.65    -> parent 2 (weights 2,3,4: 5.4 -> parent 0);
+                                 loop .2 -> m, only neighbour 3                       -> 3
+             .95*1.0833=1.029 -> parent 0; loop .1 -> m, only neighbour 1             -> 1
+    gen 1: population [3,3,1]; by estimate [3,3,1]; distinct top 2 = [3,1]; measure 3 (1.2);
+           top1 = 3 (1.2); |1.2-1.5|/1.5 = .2: go on; best = (3, 1.2).
+           weights 1,1,1/2, cumulative 1, 2, 2.5:
+             .5*2.5=1.25   -> second member, parent 3 (weights 1,1,2: 2.0 -> parent 1);
+                              loop .9 -> n, only neighbour 1                          -> 1
+             .85*2.5=2.125 -> parent 1; loop .4 -> m, only neighbour 0                -> 0
+             .1*2.5=.25    -> parent 3; loop .3 -> m, only neighbour 2                -> 2
+    gen 2: population [1,0,2]; by estimate [1,2,0]; top 2 = [1,2], both known; top1 = 1 (1.5);
+           |1.5-1.2|/1.2 = .25: no convergence, and 1.5 is not below 1.2: best stays (3, 1.2),
+           although candidate 3 is no longer in the population.  Generation bound 3: stop."""
+    space = [((1,), (1,)), ((2,), (1,)), ((1,), (2,)), ((2,), (2,))]
+    est = [4.0, 2.0, 3.0, 1.0]
+    meas = [5.0, 1.5, 3.0, 1.2]
+    us = [0.1, 0.1, 0.1,
+          0.3, 0.7, 0.0, 0.6, 0.2, 0.0, 0.95, 0.1, 0.0,
+          0.5, 0.9, 0.0, 0.85, 0.4, 0.0, 0.1, 0.3, 0.0]
+    rng = Scripted(us)
+    r = sr.heuristic_search(space, est, lambda c: meas[c], N=3, n=2, epsilon=0.01, seed=0, max_generations=3, rng=rng)
+    assert r["populations"] == [[0, 1, 2], [3, 3, 1], [1, 0, 2]]
+    assert r["log"] == [(0, 1, 2.0, 1.5), (0, 2, 3.0, 3.0), (1, 3, 1.0, 1.2)]
+    assert (r["best"], r["best_t"], r["converged"], r["generations"]) == (3, 1.2, False, 3)
+    assert rng.k == len(us)
+
+
+def test_first_run_populations():
+    """The populations of the first hand-traced run, as its docstring derives them."""
+    space = [((1,), (1,)), ((2,), (1,)), ((1,), (2,)), ((2,), (2,))]
+    us = [0.1, 0.6, 0.3,
+          0.9, 0.7, 0.5, 0.1, 0.2, 0.0, 0.5, 0.1, 0.3,
+          0.5, 0.9, 0.2, 0.7, 0.4, 0.6, 0.99, 0.0, 0.8]
+    r = sr.heuristic_search(space, [4.0, 2.0, 3.0, 1.0], lambda c: [5.0, 1.5, 3.0, 2.5][c], N=3, n=2, epsilon=0.01,
+                            seed=0, rng=Scripted(us))
+    assert r["populations"] == [[0, 2, 1], [2, 0, 3], [1, 3, 1]]
+
+
 def _grid_space(ms, ns):
     return [((m,), (n,)) for m, n in itertools.product(ms, ns)]
 
