@@ -167,6 +167,9 @@ int mcf_list_variants3(const mcf_problem *problem, int64_t P, int softmax, int32
  * pair mb, rg; n: the pair ns, nj; h: T_L) replaced by that of a random feasible variant that
  * differs in that loop only.  A candidate is measured at most once.  Random numbers are SplitMix64 of
  * (seed + counter).  Zero fields of *params read as the defaults 32, 8, 16 and 0.02.
+ * One deviation from the listing: the convergence test only ends the search; what is returned
+ * is the fastest candidate measured in any generation (the listing returns the fastest of the
+ * last generation's shortlist, which may be up to epsilon slower than one measured earlier).
  */
 typedef struct mcf_search_params {
     int32_t population;      /* N of Alg. 1 (default 32)                                   */

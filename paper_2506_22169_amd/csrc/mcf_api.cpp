@@ -17,6 +17,22 @@ static void packed(int64_t out[3], int64_t rows, int64_t cols) {
     out[0] = rows * cols; out[1] = cols; out[2] = 1;
 }
 
+// An output [batch, rows, cols] (col stride 1): a batch must end before the next one starts.
+static bool batches_disjoint(int64_t batch, int64_t rows, int64_t cols, const int64_t s[3]) {
+    if (batch <= 1 || rows <= 0 || cols <= 0) return true;
+    if (s[1] > (1ll << 40) || rows > (1ll << 31)) return false; // keeps the product below in range
+    return s[0] >= (rows - 1) * s[1] + cols;
+}
+
+// Whether 1 + (batch-1) s0 + (rows-1) s1 + (cols-1) s2 stays below 2^60 elements.
+static bool span_fits(int64_t batch, int64_t rows, int64_t cols, const int64_t s[3]) {
+    const int64_t n[3] = {batch, rows, cols};
+    __int128 total = 1;
+    for (int d = 0; d < 3; ++d)
+        if (n[d] > 1) total += (__int128)(n[d] - 1) * s[d];
+    return total < ((__int128)1 << 60);
+}
+
 int decode_layout(const mcf_problem *p, Layout *o) {
     if (p->in_dtype != MCF_F16 && p->in_dtype != MCF_BF16) return MCF_EUNSUPPORTED;
     if (p->out_dtype != p->in_dtype) return MCF_EUNSUPPORTED;
@@ -46,6 +62,13 @@ int decode_layout(const mcf_problem *p, Layout *o) {
     if (p->N > 1 && o->sd[1] < p->L) return MCF_EINVAL;
     if (p->M > 1 && o->se[1] < p->L) return MCF_EINVAL;
     if (o->b_kcontig ? (p->N > 1 && o->sb[2] < p->K) : (p->K > 1 && o->sb[1] < p->N)) return MCF_EINVAL;
+    // Batches of the output must not overlap one another: blocks of different batches would
+    // store to the same rows.  (The inputs are only read: a zero or overlapping batch stride
+    // is a legal broadcast there.)
+    if (!batches_disjoint(p->batch, p->M, p->L, o->se)) return MCF_EINVAL;
+    // and every tensor's extent in elements must fit 64-bit arithmetic with room to spare
+    for (int t = 0; t < 4; ++t)
+        if (!span_fits(p->batch, rows[t], cols[t], out[t])) return MCF_EUNSUPPORTED;
     // 16-byte vector accesses: leading strides and batch strides in multiples of 8 elements
     const int64_t lead[4] = {o->sa[1], o->b_kcontig ? o->sb[2] : o->sb[1], o->sd[1], o->se[1]};
     const int64_t bstr[4] = {o->sa[0], o->sb[0], o->sd[0], o->se[0]};
@@ -128,6 +151,8 @@ static int run(const mcf_problem *p_in, int softmax, float scale, const void *A,
         if ((p->M > 1 && sg[1] < P) || (p->L > 1 && sf[1] < P)) return MCF_EINVAL;
         if (sg[1] % 8 || sg[0] % 8 || sf[1] % 8 || sf[0] % 8) return MCF_EALIGN;
         if (sg[1] >= (1ll << 21) || sf[1] >= (1ll << 21)) return MCF_EUNSUPPORTED;
+        if (!batches_disjoint(p->batch, p->M, P, sg)) return MCF_EINVAL;
+        if (!span_fits(p->batch, p->M, P, sg) || !span_fits(p->batch, p->L, P, sf)) return MCF_EUNSUPPORTED;
     }
     Layout lay;
     int st = decode_layout(p, &lay);

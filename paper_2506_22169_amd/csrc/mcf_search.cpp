@@ -47,101 +47,151 @@ std::vector<int> neighbours(const std::vector<mcf_tiles> &space, int i, int loop
 } // namespace
 } // namespace mcf
 
+namespace mcf {
+namespace {
+
+// State of one search: the candidate space with its model estimates, what has been measured so
+// far, and the generation in hand.  A generation is a multiset of candidate indices.
+class TileSearch {
+  public:
+    TileSearch(std::vector<mcf_tiles> space, int members, int shortlist, uint64_t seed, mcf_measure_fn fn, void *user,
+               mcf_search_report *report)
+        : space_(std::move(space)), members_(members), shortlist_(shortlist), rng_(seed), fn_(fn), user_(user),
+          report_(report), time_(space_.size(), -1.0) {}
+
+    // Generation 0: a random order of the whole space, cut to `members` or topped up with
+    // independent draws (a space no larger than a generation is covered at once).
+    void seed_generation() {
+        const int C = (int)space_.size();
+        std::vector<int> order(C);
+        for (int i = 0; i < C; ++i) order[i] = i;
+        gen_.resize(members_);
+        for (int i = 0; i < members_; ++i) {
+            if (i < C) {
+                std::swap(order[i], order[i + rng_.below(C - i)]);
+                gen_[i] = order[i];
+            } else {
+                gen_[i] = rng_.below(C);
+            }
+        }
+    }
+
+    // Orders the generation by the model (ties by index), times the first `shortlist` distinct
+    // members that have no time yet, and returns the fastest of that shortlist; -1 if a
+    // measurement failed.
+    int evaluate(int generation) {
+        std::sort(gen_.begin(), gen_.end(), [&](int a, int b) {
+            return space_[a].t_est_s != space_[b].t_est_s ? space_[a].t_est_s < space_[b].t_est_s : a < b;
+        });
+        int front = -1, taken = 0;
+        std::vector<char> seen(space_.size(), 0);
+        for (int c : gen_) {
+            if (seen[c]) continue;
+            seen[c] = 1;
+            if (time_[c] < 0.0) {
+                const double t = fn_(&space_[c], user_);
+                if (!(t >= 0.0) || !(t < INFINITY)) return -1;
+                time_[c] = t;
+                record(c, generation);
+                if (overall_ < 0 || t < time_[overall_]) overall_ = c;
+            }
+            if (front < 0 || time_[c] < time_[front]) front = c;
+            if (++taken == shortlist_) break;
+        }
+        return front;
+    }
+
+    // Next generation: each member descends from a member of this one, chosen with probability
+    // proportional to 1 / estimate, with the tile choice of one loop replaced by that of a
+    // random candidate that differs there only (none: the member is carried over).
+    void breed() {
+        std::vector<double> upto(gen_.size());
+        double total = 0.0;
+        for (size_t i = 0; i < gen_.size(); ++i) upto[i] = (total += 1.0 / space_[gen_[i]].t_est_s);
+        std::vector<int> next(gen_.size());
+        for (int &child : next) {
+            const double mark = rng_.next() * total;
+            const size_t at = std::upper_bound(upto.begin(), upto.end(), mark) - upto.begin();
+            const int parent = gen_[std::min(at, gen_.size() - 1)];
+            const int loop = rng_.below(kLoops);
+            const double u = rng_.next();
+            const std::vector<int> other = neighbours(space_, parent, loop);
+            child = other.empty() ? parent : other[std::min((size_t)(u * other.size()), other.size() - 1)];
+        }
+        gen_.swap(next);
+    }
+
+    double time_of(int c) const { return time_[c]; }
+    int fastest_measured() const { return overall_; }
+    int measured() const { return n_measured_; }
+    const mcf_tiles &tiles(int c) const { return space_[c]; }
+
+  private:
+    void record(int c, int generation) {
+        if (report_ && n_measured_ < MCF_SEARCH_LOG_MAX) {
+            mcf_search_entry &e = report_->log[n_measured_];
+            const mcf_tiles &t = space_[c];
+            e.mb = t.mb; e.rg = t.rg; e.ns = t.ns; e.nj = t.nj;
+            e.generation = generation; e.tl = t.tl; e.t_est_s = t.t_est_s; e.t_meas_s = time_[c];
+        }
+        ++n_measured_;
+    }
+
+    std::vector<mcf_tiles> space_;
+    int members_, shortlist_;
+    Uniforms rng_;
+    mcf_measure_fn fn_;
+    void *user_;
+    mcf_search_report *report_;
+    std::vector<double> time_; // measured seconds per candidate, < 0: not measured
+    std::vector<int> gen_;
+    int overall_ = -1;         // fastest candidate measured so far, over all generations
+    int n_measured_ = 0;
+};
+
+} // namespace
+} // namespace mcf
+
 using namespace mcf;
 
 extern "C" int mcf_search_tiles(const mcf_problem *p, int softmax, const mcf_search_params *params,
                                 mcf_measure_fn measure, void *user, mcf_tiles *best, mcf_search_report *report) {
     if (!measure || !best) return MCF_EINVAL;
     std::vector<mcf_tiles> space;
-    int st = feasible_candidates(p, softmax, &space);
+    const int st = feasible_candidates(p, softmax, &space);
     if (st != MCF_OK) return st;
-    const int N = params && params->population > 0 ? params->population : 32;
-    const int n = params && params->top_n > 0 ? params->top_n : 8;
+    const int members = params && params->population > 0 ? params->population : 32;
+    const int shortlist = params && params->top_n > 0 ? params->top_n : 8;
     const int max_gen = params && params->max_generations > 0 ? params->max_generations : 16;
     const double eps = params && params->epsilon > 0 ? params->epsilon : 0.02;
-    Uniforms rng(params ? params->seed : 0);
-    const int C = (int)space.size();
-
     if (report) {
         memset(report, 0, sizeof(*report));
-        report->space = C;
+        report->space = (int)space.size();
     }
-    // first population: without repetition while unused candidates remain (a random permutation
-    // of the space), topped up with random draws
-    std::vector<int> population(N), perm(C);
-    for (int i = 0; i < C; ++i) perm[i] = i;
-    for (int i = 0; i < N; ++i) {
-        if (i < C) {
-            const int j = i + rng.below(C - i);
-            std::swap(perm[i], perm[j]);
-            population[i] = perm[i];
-        } else {
-            population[i] = rng.below(C);
-        }
-    }
-    std::vector<double> measured(C, -1.0);
-    double best_t = 1e9;
-    int best_cand = -1, generation = 0, n_measured = 0;
+    TileSearch search(std::move(space), members, shortlist, params ? params->seed : 0, measure, user, report);
+    search.seed_generation();
+    // The search stops when the fastest of a generation's shortlist is within eps (relative) of
+    // the time the previous generations had settled on; what is returned is the fastest
+    // candidate measured in any generation.
+    double settled = 1e9;
+    int generation = 0;
     bool converged = false;
-    for (;;) {
-        // rank by the model; ties by candidate index
-        std::sort(population.begin(), population.end(), [&](int a, int b) {
-            return space[a].t_est_s != space[b].t_est_s ? space[a].t_est_s < space[b].t_est_s : a < b;
-        });
-        std::vector<int> topk;
-        for (int c : population) {
-            if (std::find(topk.begin(), topk.end(), c) == topk.end()) topk.push_back(c);
-            if ((int)topk.size() == n) break;
-        }
-        for (int c : topk) {
-            if (measured[c] >= 0.0) continue;
-            const double t = measure(&space[c], user);
-            if (!(t >= 0.0) || !(t < INFINITY)) return MCF_ELAUNCH;
-            measured[c] = t;
-            if (report && n_measured < MCF_SEARCH_LOG_MAX) {
-                mcf_search_entry &e = report->log[n_measured];
-                e.mb = space[c].mb; e.rg = space[c].rg; e.ns = space[c].ns; e.nj = space[c].nj;
-                e.generation = generation; e.tl = space[c].tl; e.t_est_s = space[c].t_est_s; e.t_meas_s = t;
-            }
-            ++n_measured;
-        }
-        int top1 = topk[0];
-        for (int c : topk)
-            if (measured[c] < measured[top1]) top1 = c;
-        const double top1_t = measured[top1];
+    while (!converged && generation < max_gen) {
+        const int front = search.evaluate(generation);
+        if (front < 0) return MCF_ELAUNCH;
         ++generation;
-        if (fabs(top1_t - best_t) / best_t < eps) {
-            best_cand = top1; best_t = top1_t; converged = true;
-            break;
-        }
-        if (top1_t < best_t) { best_cand = top1; best_t = top1_t; }
-        if (generation >= max_gen) break;
-        // next population: parents with probability ~ 1 / estimate, one loop's choice replaced
-        std::vector<double> cumulative(N);
-        double total = 0.0;
-        for (int i = 0; i < N; ++i) {
-            total += 1.0 / space[population[i]].t_est_s;
-            cumulative[i] = total;
-        }
-        std::vector<int> next(N);
-        for (int i = 0; i < N; ++i) {
-            const double target = rng.next() * total;
-            int parent = population[N - 1];
-            for (int q = 0; q < N; ++q)
-                if (target < cumulative[q]) { parent = population[q]; break; }
-            const int loop = rng.below(kLoops);
-            const double u = rng.next();
-            const std::vector<int> options = neighbours(space, parent, loop);
-            next[i] = options.empty() ? parent : options[std::min((int)(u * options.size()), (int)options.size() - 1)];
-        }
-        population.swap(next);
+        const double t = search.time_of(front);
+        converged = fabs(t - settled) / settled < eps;
+        if (converged || t < settled) settled = t;
+        if (!converged && generation < max_gen) search.breed();
     }
-    *best = space[best_cand];
+    const int winner = search.fastest_measured();
+    *best = search.tiles(winner);
     if (report) {
         report->generations = generation;
-        report->measured = std::min(n_measured, (int)MCF_SEARCH_LOG_MAX);
+        report->measured = std::min(search.measured(), (int)MCF_SEARCH_LOG_MAX);
         report->converged = converged ? 1 : 0;
-        report->best_t_s = best_t;
+        report->best_t_s = search.time_of(winner);
     }
     return MCF_OK;
 }

@@ -50,6 +50,16 @@ def test_validation_codes_without_a_launch():
     assert call(make_problem(2, 64, 64, 64, 64, "f16", a_stride=(64 * 72, 72, 2))) == 2   # A not K-contiguous
     assert call(make_problem(2, 64, 64, 64, 64, "f16", a_stride=(64 * 68, 68, 1))) == 3   # row stride % 8
     assert call(make_problem(2, 64, 64, 64, 64, "f16", d_stride=(64 * 32, 32, 1))) == 1   # rows overlap
+    # layout rules are also what the host-only picker checks (no launch can follow from it)
+    tt = Tiles()
+    pick = lambda prob: lib.mcf_pick_tiles(ctypes.byref(prob), 0, ctypes.byref(tt))
+    assert call(make_problem(2, 64, 64, 64, 64, "f16", e_stride=(0, 64, 1))) == 1         # batches of E on top of one another
+    assert pick(make_problem(2, 64, 64, 64, 64, "f16", e_stride=(63 * 64 + 56, 64, 1))) == 1  # ... overlapping by one piece
+    assert pick(make_problem(2, 64, 64, 64, 64, "f16", e_stride=(63 * 64 + 64, 64, 1))) == 0  # ... exactly adjacent: fine
+    assert pick(make_problem(1, 64, 64, 64, 64, "f16", e_stride=(0, 64, 1))) == 0         # one batch: its stride is not used
+    assert pick(make_problem(2, 64, 64, 64, 64, "f16", a_stride=(0, 64, 1))) == 0         # a broadcast input is legal
+    assert pick(make_problem(2, 64, 64, 64, 64, "f16", a_stride=(1 << 61, 64, 1))) == 2   # extent beyond 64-bit arithmetic
+    assert call(make_problem(1 << 30, 64, 64, 64, 64, "f16", e_stride=(1 << 40, 64, 1))) == 2
     assert call(p, [ctypes.c_void_p(4096 + 2)] + fake[1:]) == 3                          # misaligned pointer
     assert call(p, [fake[3]] + fake[1:]) == 1                                            # E aliases A
     assert call(p, [None] + fake[1:]) == 1                                               # null pointer

@@ -1,6 +1,7 @@
 """The library's heuristic search (mcf_search_tiles, Sec. IV-B Alg. 1) against the oracle's, on
 the same candidate space, estimates, seed and measurement: the same candidates are measured in
-the same order and the same one is returned.  Host only: the measurement is a table."""
+the same order and the search ends in the same generation; the library then returns the fastest
+candidate it measured.  Host only: the measurement is a table."""
 import ctypes
 
 import pytest
@@ -53,10 +54,17 @@ def test_library_search_equals_oracle_search(name, N, n, seed):
     assert calls == [shapes[c] for _, c, _, _ in want["log"]]
     got_log = [(e.generation, (e.mb, e.rg, e.ns, e.nj, e.tl), e.t_est_s, e.t_meas_s) for e in rep.entries()]
     assert got_log == [(g, shapes[c], est[c], t) for g, c, _, t in want["log"]]
-    assert (best.mb, best.rg, best.ns, best.nj, best.tl) == shapes[want["best"]]
-    assert rep.best_t_s == want["best_t"]
     assert (rep.generations, bool(rep.converged)) == (want["generations"], want["converged"])
-    assert best.t_est_s == est[want["best"]]
+    # The library returns the fastest candidate measured in any generation (first in measurement
+    # order among equals); Alg. 1 as printed returns the fastest of the last shortlist when it
+    # converges, which is within epsilon of it, and the same candidate otherwise.
+    fastest = min(want["log"], key=lambda e: e[3])
+    assert (best.mb, best.rg, best.ns, best.nj, best.tl) == shapes[fastest[1]]
+    assert rep.best_t_s == fastest[3] and best.t_est_s == est[fastest[1]]
+    if want["converged"]:
+        assert rep.best_t_s <= want["best_t"] < rep.best_t_s * 1.02 / (1 - 0.02)
+    else:
+        assert rep.best_t_s == want["best_t"] and fastest[1] == want["best"]
 
 
 def test_defaults_and_errors():
