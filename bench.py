@@ -7,15 +7,25 @@ synthetic input.  Inputs are resident in HBM before the timed region starts.  Be
 small workloads fit in the 256 MB memory-side cache, steps rotate over enough distinct
 input/output sets (> 768 MiB in total) that every step's operands come from HBM.
 
-The K timed steps are captured once into a HIP graph (each step is still one call of the
-C ABI on the capturing stream) and replayed, so the figure is device throughput and not the
-Python call overhead; --eager times plain calls instead.
+Protocol (the same for every workload and for the ceilings):
+  1. --warmup untimed steps (they also set kernel attributes before any capture);
+  2. the --steps steps are captured once into a HIP graph (each step is still one call of the
+     C ABI on the capturing stream; the host-side tile pick runs at capture);
+  3. an untimed clock ramp: the graph is replayed until at least RAMP_MS of device time have
+     passed, whatever --warmup says (a cold engine clock makes a launch up to a third slower);
+  4. the timed region is `replays` back-to-back replays of that graph, as many as it takes to
+     fill MIN_REGION_MS, bracketed by synchronize on both sides.  `ms_per_step` and `value`
+     come from the host clock around the region divided by steps x replays;
+     `us_per_launch_events` from HIP events on the launch stream around the same region.
+--eager times plain calls instead of graph replays (the tile pick is then inside every step).
 
 Prints ONE JSON line: the BASELINE metric (effective HBM GB/s on compulsory bytes) with a
 `roofline` object for the chain kernel and a `cpu_baseline` object (the fp64 oracle timed on
-this host's cores).  The metric is quoted per configuration: a default run also times the other
-four configurations after the timed region (one child process each, same protocol, 1000 steps;
-the long attention 40) and reports them under `per_config`; `value` stays cfg2's.
+this host's cores).  The metric is quoted per configuration: a default run also measures the
+other four configurations after the timed region (one child process each, same protocol) and
+reports them under `per_config`, each with its own roofline, parity and cpu_baseline; `value`
+stays cfg2's.  --ceilings measures, with the same protocol, what bounds the kernel on this
+machine: a streaming copy, a loop of MFMAs only and an empty kernel.
 """
 import argparse
 import json
@@ -29,15 +39,18 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
 MFMA_PEAK_TFLOPS = 2500.0  # dense fp16 / bf16
+RAMP_MS = 150.0            # untimed launches before anything is timed
+MIN_REGION_MS = 20.0       # the timed region is at least this long
+CPU_SAMPLE_FLOPS = 2.0e10  # fp64 work given to the oracle per workload (a few seconds of the host's cores)
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--steps", type=int, default=2000, help="steps per captured graph (the timed region replays it)")
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="cfg2", help="cfg1..cfg5 (default: cfg2, the configuration the metric is quoted on), or a row of the "
-                                                      "paper's shape tables: G1..G12, S1..S5, S7..S9")
+                                                      "paper's shape tables: G1..G12, S1..S9")
     ap.add_argument("--tiles", default=None, help="mb,rg,ns,nj[,tl] to override the picker")
     ap.add_argument("--tune", action="store_true",
                     help="choose the tiles by the measured search (Alg. 1) before the warm-up instead of by the "
@@ -49,15 +62,112 @@ def parse_args():
     ap.add_argument("--warm", action="store_true", help="reuse one buffer set (cache-resident operands)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-config", action="store_true",
-                    help="with the default workload (and the CPU baseline leg on) the other four configurations are timed "
-                         "as well (child processes, after the timed region) and reported under 'per_config'; this "
-                         "switches that off")
+                    help="with the default workload the other four configurations are measured as well (child "
+                         "processes, after the timed region) and reported under 'per_config'; this switches that off")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="measure the machine's ceilings instead of the chain: device copy (16 MiB and 1 GiB of "
+                         "traffic), MFMA-only loop, empty kernel; one JSON line")
     ap.add_argument("--copy-ref", type=int, default=0, metavar="MiB",
                     help="after the timed region also run one plain device copy of this many MiB (the "
                          "known-size kernel that calibrates the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--traffic", default=os.path.join(ROOT, "profiles", "traffic.json"),
                     help="JSON file with measured HBM bytes per launch (from the rocprofv3 --pmc runs)")
     return ap.parse_args()
+
+
+class Timer:
+    """The protocol of the module docstring around any `step(i)`."""
+
+    def __init__(self, torch, steps, warmup, eager=False):
+        self.torch, self.steps, self.warmup, self.eager = torch, steps, warmup, eager
+
+    def measure(self, step):
+        torch = self.torch
+        for i in range(max(self.warmup, 1)):
+            step(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        graph = None
+        if not self.eager:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):      # the binding launches on torch's current (capturing) stream
+                for i in range(self.steps):
+                    step(i)
+
+        def once():
+            if graph is not None:
+                graph.replay()
+            else:
+                for i in range(self.steps):
+                    step(i)
+        # clock ramp: untimed passes, back to back, until RAMP_MS of device time have passed
+        # (replays keep the device busy; plain calls from Python would leave it idle most of the time)
+        ramp_launches, ramp_ms, passes = 0, 0.0, 1
+        while ramp_ms < RAMP_MS:
+            e0.record()
+            for _ in range(passes):
+                once()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            ramp_ms += ms
+            ramp_launches += passes * self.steps
+            once_ms = ms / passes
+            passes = int(min(10000, max(1, 30.0 / max(once_ms, 1e-4))))       # aim at 30 ms between synchronisations
+        replays = max(1, int(math.ceil(MIN_REGION_MS / max(once_ms, 1e-3))))
+        # ---- timed region: `replays` x `steps` steps ---------------------------------------
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(replays):
+            once()
+        e1.record()
+        torch.cuda.synchronize()
+        wall_s = time.perf_counter() - t0
+        dev_s = e0.elapsed_time(e1) * 1e-3
+        n = self.steps * replays
+        return {"t_step": wall_s / n, "t_kernel": dev_s / n, "replays": replays, "clock_ramp_launches": ramp_launches,
+                "clock_ramp_ms": ramp_ms}
+
+
+def run_ceilings(args, torch, mcf):
+    """The machine's ceilings under the protocol of the chain: copy, MFMA-only, empty kernel."""
+    out = {"kind": "ceilings", "steps": args.steps, "warmup": args.warmup}
+    timer = Timer(torch, args.steps, args.warmup)
+
+    def copy_case(total_bytes, rotate_bytes):
+        half = total_bytes // 2                                 # read half, write half
+        n_sets = max(2, min(64, rotate_bytes // total_bytes))
+        srcs = [torch.full((half // 2,), 1.0, dtype=torch.float16, device="cuda") for _ in range(n_sets)]
+        dsts = [torch.empty_like(s) for s in srcs]
+        r = timer.measure(lambda i: mcf.probe_copy(dsts[i % n_sets], srcs[i % n_sets]))
+        assert bool((dsts[0] == 1.0).all())
+        return {"traffic_bytes": total_bytes, "buffer_sets": n_sets, "us_per_launch": r["t_kernel"] * 1e6,
+                "gbs": total_bytes / r["t_kernel"] / 1e9, "frac_of_hbm_peak": total_bytes / r["t_kernel"] / 1e9 / HBM_PEAK_GBS,
+                "replays": r["replays"]}
+
+    out["copy_16MiB"] = copy_case(16 * 2**20, 1024 * 2**20)     # cfg2's compulsory bytes, operands from HBM
+    out["copy_24MiB"] = copy_case(24 * 2**20, 1024 * 2**20)     # cfg3's
+    out["copy_1GiB"] = copy_case(2**30, 4 * 2**30)
+    buf = torch.empty(2048 * 8 * 64, dtype=torch.float32, device="cuda")
+    for waves, blocks in ((4, 256), (8, 256), (4, 512)):
+        iters = 64
+        r = timer.measure(lambda i: mcf.probe_mfma(buf, blocks, waves, iters))
+        flops = blocks * waves * iters * 8 * 32768
+        out[f"mfma_{blocks}x{waves}w"] = {"us_per_launch": r["t_kernel"] * 1e6, "flops": flops,
+                                           "tflops": flops / r["t_kernel"] / 1e12,
+                                           "frac_of_mfma_peak": flops / r["t_kernel"] / 1e12 / MFMA_PEAK_TFLOPS}
+    # long loop: the launch is amortised, what remains is the sustained matrix rate
+    iters = 4096
+    r = Timer(torch, 50, 5).measure(lambda i: mcf.probe_mfma(buf, 256, 8, iters))
+    flops = 256 * 8 * iters * 8 * 32768
+    out["mfma_sustained"] = {"us_per_launch": r["t_kernel"] * 1e6, "flops": flops, "tflops": flops / r["t_kernel"] / 1e12,
+                             "frac_of_mfma_peak": flops / r["t_kernel"] / 1e12 / MFMA_PEAK_TFLOPS}
+    for blocks in (1, 256, 2048):
+        r = timer.measure(lambda i: mcf.probe_empty(blocks))
+        out[f"empty_{blocks}"] = {"us_per_launch": r["t_kernel"] * 1e6}
+    print(json.dumps(out))
+    return 0
 
 
 def main():
@@ -78,6 +188,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     mcf.load_library()  # fail loudly if the HIP library is not built
+    if args.ceilings:
+        return run_ceilings(args, torch, mcf)
 
     w = mi.WORKLOADS[args.workload] if args.workload in mi.WORKLOADS else mi.PAPER_SHAPES[args.workload]
     tdt = torch.float16 if w.dtype == "f16" else torch.bfloat16
@@ -162,38 +274,15 @@ def main():
                   "best_us": rep.best_t_s * 1e6,
                   "log": [[e.generation, e.mb, e.rg, e.ns, e.nj, e.tl, round(e.t_est_s * 1e6, 3), round(e.t_meas_s * 1e6, 3)]
                           for e in rep.entries()]}
-    picked = mcf.pick_tiles(prob, w.softmax) if tiles is None else mcf.eval_tiles(prob, *tiles, softmax=w.softmax)
+    # the tile pick on the host (what a step does before its launch): timed on its own
+    tp0 = time.perf_counter()
+    for _ in range(200):
+        picked_auto = mcf.pick_tiles(prob, w.softmax)
+    pick_us = (time.perf_counter() - tp0) / 200 * 1e6
+    picked = picked_auto if tiles is None else mcf.eval_tiles(prob, *tiles, softmax=w.softmax)
 
-    # ---- warm-up (also sets kernel attributes before any capture) -------------------------
-    for i in range(max(args.warmup, 1)):
-        step(i)
-    torch.cuda.synchronize()
-
-    graph = None
-    if not args.eager:
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):      # the binding launches on torch's current (capturing) stream
-            for i in range(args.steps):
-                step(i)
-        graph.replay()  # one untimed replay
-        torch.cuda.synchronize()
-
-    # ---- timed region: exactly K steps ------------------------------------------------------
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    ev0.record()
-    if graph is not None:
-        graph.replay()
-    else:
-        for i in range(args.steps):
-            step(i)
-    ev1.record()
-    torch.cuda.synchronize()
-    wall_s = time.perf_counter() - t0
-    dev_s = ev0.elapsed_time(ev1) * 1e-3
-    t_step = wall_s / args.steps          # whole-job figure: host clock around the region
-    t_kernel = dev_s / args.steps         # HIP events on the launch stream: average per launch
+    m = Timer(torch, args.steps, args.warmup, args.eager).measure(step)
+    t_step, t_kernel = m["t_step"], m["t_kernel"]
 
     if args.copy_ref:
         n = args.copy_ref * 2**20 // 2
@@ -212,7 +301,7 @@ def main():
     else:
         achieved, peak, unit = flops / t_kernel / 1e12, MFMA_PEAK_TFLOPS, "TFLOP/s"
     traffic = None
-    if args.traffic and os.path.exists(args.traffic):
+    if args.traffic and os.path.exists(args.traffic) and not args.chain3:
         traffic = json.load(open(args.traffic)).get(args.workload)
 
     # ---- parity of set 0 at the benchmarked configuration + oracle timing ------------------
@@ -223,15 +312,15 @@ def main():
         step(0)
         torch.cuda.synchronize()
         full_flops = flops
-        nb = w.batch if full_flops <= 2.0e10 else max(1, int(w.batch * 2.0e10 / full_flops))
+        nb = w.batch if full_flops <= CPU_SAMPLE_FLOPS else max(1, int(w.batch * CPU_SAMPLE_FLOPS / full_flops))
         rows = None
         A64 = mi.from_bits(x["a_bits"][:nb], w.dtype)
         B64 = mi.from_bits(x["b_bits"][:nb], w.dtype)
         B64 = B64.transpose(0, 2, 1) if w.softmax else B64
         D64 = mi.from_bits(x["d_bits"][:nb], w.dtype)
-        if full_flops > 2.0e10 and not args.chain3:   # long-sequence workload: a bounded sample of rows of one head
+        if full_flops > CPU_SAMPLE_FLOPS and not args.chain3:   # long-sequence workload: a bounded sample of rows of one head
             rng = np.random.default_rng(0)
-            n_rows = max(64, int(2.0e10 / (2.0 * w.N * (w.K + w.L))))
+            n_rows = max(64, int(CPU_SAMPLE_FLOPS / (2.0 * w.N * (w.K + w.L))))
             rows = np.stack([np.zeros(n_rows, dtype=np.int64), rng.integers(0, w.M, n_rows)], axis=1)
         tc = time.perf_counter()
         if rows is None:
@@ -258,6 +347,7 @@ def main():
                   "tolerance": 1e-2, "checked": sample}
         parity["ok"] = bool(parity["max_abs_err"] <= 1e-2 * parity["max_abs_ref"])
 
+    roofline = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak, "traffic": traffic}
     out = {
         "metric": "fused-chain effective HBM GB/s (% of peak) and TFLOP/s per config",
         "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -268,34 +358,38 @@ def main():
                    "tiles": {"mb": picked.mb, "rg": picked.rg, "ns": picked.ns, "nj": picked.nj, "tm": picked.tm,
                              "tn": picked.tn, "tk": picked.tk, "tl": picked.tl, "stages": picked.stages},
                    "buffer_sets": n_sets, "launch": "eager" if args.eager else "hip_graph",
+                   "replays": m["replays"], "timed_steps": args.steps * m["replays"],
+                   "clock_ramp_launches": m["clock_ramp_launches"], "clock_ramp_ms": round(m["clock_ramp_ms"], 1),
                    "tile_choice": "search" if search else ("given" if args.tiles else "model"), "search": search},
         "pct_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS, "tflops": tflops,
         "pct_mfma_peak": 100.0 * tflops / MFMA_PEAK_TFLOPS,
         "us_per_launch_events": t_kernel * 1e6,
+        "host_tile_pick_us": pick_us,
         "model_t_est_us": picked.t_est_s * 1e6,
-        "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-                     "frac": achieved / peak, "traffic": traffic},
+        "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "parity": parity,
     }
-    # ---- the metric is quoted per configuration: time the other four as well (context; `value` is cfg2's) ----
+    # ---- the metric is quoted per configuration: measure the other four as well (`value` is cfg2's) ----
     if (args.workload == "cfg2" and not args.no_per_config and not args.no_cpu_baseline
             and not (args.chain3 or args.tune or args.tiles or args.warm or args.eager)):
         import subprocess
-        per = {"cfg2": {"us_per_launch": t_kernel * 1e6, "gbs": gbs, "tflops": tflops, "bound": bound, "frac": achieved / peak,
-                        "tiles": [picked.mb, picked.rg, picked.ns, picked.nj, picked.tl]}}
+        per = {"cfg2": {"us_per_launch": t_kernel * 1e6, "gbs": gbs, "tflops": tflops, "roofline": roofline,
+                        "tiles": [picked.mb, picked.rg, picked.ns, picked.nj, picked.tl],
+                        "cpu_baseline": cpu_baseline, "parity_ok": parity["ok"]}}
         del sets
         torch.cuda.empty_cache()
         for name in ("cfg1", "cfg3", "cfg4", "cfg5"):
-            steps = 40 if name == "cfg5" else 1000
+            steps = 20 if name == "cfg5" else 1000    # graph length of the child; its timed region is sized by time
             try:
-                r = subprocess.run([sys.executable, os.path.abspath(__file__), "--workload", name, "--steps", str(steps), "--warmup", "50",
-                                    "--no-cpu-baseline", "--no-per-config"], capture_output=True, text=True, timeout=240)
+                r = subprocess.run([sys.executable, os.path.abspath(__file__), "--workload", name, "--steps", str(steps),
+                                    "--warmup", str(min(args.warmup, 50)), "--no-per-config"],
+                                   capture_output=True, text=True, timeout=300)
                 d = json.loads(r.stdout.strip().splitlines()[-1])
                 t = d["config"]["tiles"]
                 per[name] = {"us_per_launch": d["us_per_launch_events"], "gbs": d["value"], "tflops": d["tflops"],
-                             "bound": d["roofline"]["bound"], "frac": d["roofline"]["frac"],
-                             "tiles": [t["mb"], t["rg"], t["ns"], t["nj"], t["tl"]]}
+                             "roofline": d["roofline"], "tiles": [t["mb"], t["rg"], t["ns"], t["nj"], t["tl"]],
+                             "cpu_baseline": d["cpu_baseline"], "parity_ok": d["parity"]["ok"]}
             except Exception as e:      # context only: never fail the benchmark line over it
                 per[name] = {"error": str(e)[:200]}
         out["per_config"] = per

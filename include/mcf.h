@@ -224,6 +224,21 @@ int mcf_tune_tiles(const mcf_problem *problem, int softmax, float scale, const v
                    int launches, void *hip_stream, mcf_tiles *best,
                    mcf_search_report *report_or_null);
 
+/*
+ * Measurement aids (no part of the chain): the kernels whose times bound what the chain kernel
+ * can reach -- Sec. IV-A's W and P as this machine delivers them, and the cost of a launch.
+ * All asynchronous on hip_stream, device pointers owned by the caller, nothing allocated.
+ *   mcf_probe_copy : dst[0..bytes) = src[0..bytes), 16 bytes per lane (bytes a multiple of 16,
+ *                    pointers 16-byte aligned, buffers must not overlap).
+ *   mcf_probe_mfma : blocks x waves_per_block waves (1..8) each issue iters x 8 independent
+ *                    32x32x16 fp16 MFMAs (32768 flops each) on register operands; out receives
+ *                    blocks * waves_per_block * 64 floats.
+ *   mcf_probe_empty: a kernel of `blocks` one-wave blocks that does nothing.
+ */
+int mcf_probe_copy(void *dst, const void *src, int64_t bytes, void *hip_stream);
+int mcf_probe_mfma(void *out, int32_t blocks, int32_t waves_per_block, int32_t iters, void *hip_stream);
+int mcf_probe_empty(int32_t blocks, void *hip_stream);
+
 /* Human-readable name of a status code (static storage). */
 const char *mcf_status_string(int status);
 

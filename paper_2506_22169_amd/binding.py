@@ -103,6 +103,11 @@ def load_library():
               lib.mcf_softmax_gemm_chain, lib.mcf_search_tiles, lib.mcf_tune_tiles, lib.mcf_list_candidates,
               lib.mcf_gemm_chain3, lib.mcf_list_variants3, lib.mcf_pick_tiles3):
         f.restype = ctypes.c_int
+    lib.mcf_probe_copy.argtypes = [vp, vp, ctypes.c_int64, vp]
+    lib.mcf_probe_mfma.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp]
+    lib.mcf_probe_empty.argtypes = [ctypes.c_int32, vp]
+    for f in (lib.mcf_probe_copy, lib.mcf_probe_mfma, lib.mcf_probe_empty):
+        f.restype = ctypes.c_int
     lib.mcf_status_string.argtypes = [ctypes.c_int]
     lib.mcf_status_string.restype = ctypes.c_char_p
     lib.mcf_last_error.argtypes = []
@@ -366,3 +371,26 @@ def list_variants3(problem, P, softmax=False):
     buf = (ctypes.c_int32 * (4 * max(n, 1)))()
     lib.mcf_list_variants3(ctypes.byref(problem), int(P), int(bool(softmax)), buf, n)
     return [tuple(buf[4 * i:4 * i + 4]) for i in range(n)]
+
+
+def probe_copy(dst, src, stream=None):
+    """mcf_probe_copy: dst = src (device tensors of equal byte size), the streaming-copy ceiling."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise McfError(1, "probe_copy: sizes differ")
+    _check(load_library().mcf_probe_copy(ctypes.c_void_p(dst.data_ptr()), ctypes.c_void_p(src.data_ptr()),
+                                         ctypes.c_int64(nbytes), _stream_ptr(stream)))
+
+
+def probe_mfma(out, blocks, waves_per_block, iters, stream=None):
+    """mcf_probe_mfma: blocks x waves_per_block waves of iters x 8 MFMAs each; out is a float32
+    device tensor of at least blocks * waves_per_block * 64 elements."""
+    if out.numel() < blocks * waves_per_block * 64:
+        raise McfError(1, "probe_mfma: output too small")
+    _check(load_library().mcf_probe_mfma(ctypes.c_void_p(out.data_ptr()), int(blocks), int(waves_per_block), int(iters),
+                                         _stream_ptr(stream)))
+
+
+def probe_empty(blocks, stream=None):
+    """mcf_probe_empty: a kernel that does nothing (the launch floor)."""
+    _check(load_library().mcf_probe_empty(int(blocks), _stream_ptr(stream)))

@@ -127,6 +127,16 @@ static __device__ __forceinline__ void dma16_once(unsigned lds_addr, unsigned vo
                  : "s"(uniform(lds_addr)), "v"(voff), "s"(uniform(base))
                  : "memory", "m0");
 }
+// f(integral_constant<int, I>) for I = B .. E-1, unrolled at compile time
+template <int B, int E, typename F> static __device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (B < E) {
+        f(std::integral_constant<int, B>{});
+        static_for<B + 1, E>(f);
+    }
+}
+// Makes the value exist in vector registers at this point of the program: the optimiser may not
+// sink what computes it past later statements of the same kind (costs no instruction).
+template <typename V> static __device__ __forceinline__ void pin(V &v) { asm volatile("" : "+v"(v)); }
 template <int N> static __device__ __forceinline__ void wait_vm() {
     static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -151,7 +161,11 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     constexpr int HB = h_blocks(LD);     // 32-wide h blocks of GEMM 2 (the last may be partial)
     constexpr int KCH = KD / 8, LCH = LD / 8;                  // 16-byte chunks in a row of K / L elements
     constexpr bool KPAD = pitch_elems(KD) != KD, LPAD = pitch_elems(LD) != LD; // rows padded to a power-of-two pitch
-    constexpr int S = ring_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX, KSPLIT); // depth of the LDS ring
+    constexpr int F_EXTRA = CH3 ? chain3_f_bytes(LD, PD) + 1024 : 0;
+    constexpr int S = ring_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX, KSPLIT, F_EXTRA); // depth of the LDS ring
+    // softmax chains: software pipeline over three consecutive n-tiles (see the loop)
+    constexpr bool PIPE = pipe_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX, KSPLIT, F_EXTRA) > 0;
+    constexpr int PRE = PIPE ? S - 2 : S - 1; // n-tiles requested before the loop
     constexpr int RBA = 2 * pitch_elems(KD);                // row bytes of the A tile (rows m)
     constexpr int RBB = BKC ? 2 * pitch_elems(KD) : 2 * TN; // row bytes of the B tile (rows n / rows k)
     constexpr int RBD = 2 * pitch_elems(LD);                // row bytes of the D tile (rows n)
@@ -411,7 +425,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         }
     }
     const int n_items = KSPLIT ? n_iters * (KC + 1) : n_iters; // ring items of the whole block
-    const int n_pre = n_items < S - 1 ? n_items : S - 1;
+    const int n_pre = n_items < PRE ? n_items : PRE;
     if constexpr (KSPLIT) {
         for (int q = 0; q < n_pre; ++q) issue_item(q / (KC + 1), q % (KC + 1), q);
     } else {
@@ -441,7 +455,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     };
     if constexpr (!KSPLIT) {
         // the A loads are older than the n_pre tile groups
-        if (n_pre == S - 1) wait_vm<(S - 1) * P>();
+        if (n_pre == PRE) wait_vm<PRE * P>();
         else wait_vm<0>();
         MCF_TRACE_POINT(2);
         __syncthreads();
@@ -675,6 +689,242 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             }
             if (++cr == NI) { cr = 0; ++ct; }
             stage_c = stage_c + 1 == S ? 0 : stage_c + 1;
+        }
+    } else if constexpr (PIPE) {
+        // Software pipeline over n-tiles.  A wave's matrix work and its softmax arithmetic sit on
+        // different pipes of the SIMD, but only overlap when they alternate in ONE wave's
+        // instruction stream (an MFMA of 32 cycles hides five to six ordinary vector operations
+        // or three exponentials issued behind it; two waves a phase apart mostly queue up).  So
+        // iteration i issues, step by step, the MFMAs of GEMM 2 of tile i-1 and then of GEMM 1 of
+        // tile i+1, and after every step a slice of the softmax of tile i, none of which depends
+        // on those MFMAs:
+        //   steps [0, TA)        row maximum of tile i, then the (lazily updated) reference
+        //   steps [TA, TT)       p = exp2(c1 * s - m) in place, row-sum partials
+        //   steps [T2, TT)       conversion of finished p to 16 bit (the operand GEMM 2 of tile
+        //                        i-1 has read by then is overwritten)
+        // Tile t lives in ring slot t % S; tile i+S-2 is requested at the top of iteration i,
+        // into the slot tile i-2 left in iteration i-1.  One block barrier per iteration.
+        static_assert(S >= 4, "three live tiles and one landing");
+        constexpr int NE = 16 * NJ;       // elements of S per lane and row set in one n-tile
+        constexpr int TT = T2 + T1;       // MFMA steps of an iteration
+        constexpr int TA = TT >= 12 ? TT / 6 : (TT >= 6 ? 2 : 1);
+        constexpr int TB = TT - TA;
+        constexpr int EA = (NE + TA - 1) / TA; // elements per maximum step
+        constexpr int EB = (NE + TB - 1) / TB; // elements per exponential step
+        const int ncol0 = wn * (32 * NJ);
+        f32x16 cc[2][NJ][MB]; // C^T of the tile in the softmax and of the tile GEMM 1 is producing
+        float mx[MB], mneg[MB], corr[MB], sum0[MB], sum1[MB];
+
+        // element e of a row set <-> slice j = e / 16, accumulator register r = e % 16
+        auto vstep = [&](auto kc, auto curc, auto raggedc, int n0) __attribute__((always_inline)) {
+            constexpr int k = decltype(kc)::value, CUR = decltype(curc)::value;
+            constexpr bool MAY_BE_RAGGED = decltype(raggedc)::value;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                if constexpr (k < TA) {
+                    if constexpr (k == 0) {
+                        if (MAY_BE_RAGGED && n0 + 32 * NJ > N) { // ragged last tile: columns past N contribute nothing
+#pragma unroll
+                            for (int e = 0; e < NE; ++e)
+                                if (n0 + 32 * (e / 16) + 8 * ((e % 16) / 4) + 4 * g + (e % 4) >= N) cc[CUR][e / 16][mb][e % 16] = -INFINITY;
+                        }
+                        mx[mb] = cc[CUR][0][mb][0];
+                    }
+#pragma unroll
+                    for (int e = k * EA; e < (k + 1) * EA && e < NE; ++e) mx[mb] = fmaxf(mx[mb], cc[CUR][e / 16][mb][e % 16]);
+                    pin(mx[mb]);
+                    if constexpr (k == TA - 1) {
+                        const float m_row = xhalf_max(mx[mb]);
+                        float m_new = fmaxf(m_run[mb], m_row);
+                        if (MCF_LAZY_MAX > 0) m_new = (m_new - m_run[mb]) * c1 > (float)MCF_LAZY_MAX ? m_new : m_run[mb];
+                        corr[mb] = __builtin_amdgcn_exp2f((m_run[mb] - m_new) * c1);
+                        mneg[mb] = -m_new * c1;
+                        pin(mneg[mb]);
+                        pin(corr[mb]);
+                        m_run[mb] = m_new;
+                        sum0[mb] = 0.f;
+                        sum1[mb] = 0.f;
+                    }
+                } else {
+#pragma unroll
+                    for (int e = (k - TA) * EB; e < (k - TA + 1) * EB && e < NE; ++e) {
+                        float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(cc[CUR][e / 16][mb][e % 16], c1, mneg[mb]));
+                        pin(pv);
+                        cc[CUR][e / 16][mb][e % 16] = pv;
+                        if (e & 1) sum1[mb] += pv;
+                        else sum0[mb] += pv;
+                    }
+                    pin(sum0[mb]);
+                    pin(sum1[mb]);
+                }
+                if constexpr (k >= T2) {
+                    // elements whose exponential was issued in an earlier step, spread evenly over
+                    // the steps of GEMM 1; the last step takes what is left
+                    constexpr int done_prev = k - 1 < TA ? 0 : ((k - TA) * EB < NE ? (k - TA) * EB : NE);
+                    constexpr int quota = NE * (k - T2 + 1) / T1;
+                    constexpr int hi = k == TT - 1 ? NE : ((done_prev < quota ? done_prev : quota) & ~1);
+                    constexpr int done_prev2 = k - 2 < TA ? 0 : ((k - 1 - TA) * EB < NE ? (k - 1 - TA) * EB : NE);
+                    constexpr int quota2 = NE * (k - T2) / T1;
+                    constexpr int lo = k == T2 ? 0 : ((done_prev2 < quota2 ? done_prev2 : quota2) & ~1);
+#pragma unroll
+                    for (int e = lo; e < hi; ++e) {
+                        pop[e / 16][mb][(e % 16) / 8][e % 8] = (T)cc[CUR][e / 16][mb][e % 16];
+                        if (e % 8 == 7) pin(pop[e / 16][mb][(e % 16) / 8]); // a finished operand
+                    }
+                }
+            }
+        };
+        auto ring_off = [&](int t) __attribute__((always_inline)) { return (unsigned)((t % S) * STAGE); }; // t >= 0
+        auto g2_step = [&](auto tc, const v8 &x) __attribute__((always_inline)) {
+            constexpr int t = decltype(tc)::value, j = t / (2 * HB), hb = (t / 2) % HB, qp = t % 2;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) accE[mb][hb] = M_::run(x, pop[j][mb][qp], accE[mb][hb]);
+        };
+        auto g1_step = [&](auto tc, auto nxtc, const v8 &x) __attribute__((always_inline)) {
+            constexpr int t = decltype(tc)::value, j = t / KS, ks = t % KS, NXT = decltype(nxtc)::value;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                if constexpr (ks == 0) {
+                    f32x16 zero;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+                    cc[NXT][j][mb] = M_::run(x, a[mb][ks], zero);
+                } else {
+                    cc[NXT][j][mb] = M_::run(x, a[mb][ks], cc[NXT][j][mb]);
+                }
+            }
+        };
+        auto fetch_d = [&](auto tc) __attribute__((always_inline)) -> v8 {
+            constexpr int t = decltype(tc)::value;
+            return load_d(t / (2 * HB), (t / 2) % HB, t % 2);
+        };
+        auto fetch_b = [&](auto tc) __attribute__((always_inline)) -> v8 {
+            constexpr int t = decltype(tc)::value;
+            return load_b(t / KS, t % KS);
+        };
+        // GEMM 2 of tile t alone / GEMM 1 of tile t alone (the ends of the pipeline)
+        auto g2_only = [&](int t) __attribute__((always_inline)) {
+            set_d_slot(ring_off(t));
+            v8 op[T2];
+            static_for<0, (PF < T2 ? PF : T2)>([&](auto tc) { op[decltype(tc)::value] = fetch_d(tc); });
+            static_for<0, T2>([&](auto tc) {
+                constexpr int t_ = decltype(tc)::value;
+                if constexpr (t_ + PF < T2) op[t_ + PF] = fetch_d(std::integral_constant<int, t_ + PF>{});
+                g2_step(tc, op[t_]);
+                __builtin_amdgcn_sched_barrier(0x406);
+            });
+        };
+        auto g1_only = [&](auto nxtc, int t) __attribute__((always_inline)) {
+            set_b_slot(ring_off(t));
+            v8 op[T1];
+            static_for<0, (PF < T1 ? PF : T1)>([&](auto tc) { op[decltype(tc)::value] = fetch_b(tc); });
+            static_for<0, T1>([&](auto tc) {
+                constexpr int t_ = decltype(tc)::value;
+                if constexpr (t_ + PF < T1) op[t_ + PF] = fetch_b(std::integral_constant<int, t_ + PF>{});
+                g1_step(tc, nxtc, op[t_]);
+                __builtin_amdgcn_sched_barrier(0x406);
+            });
+        };
+        // what follows the softmax of a tile: the row sum, and the accumulators (which hold the
+        // tiles before it, GEMM 2 of the previous tile included) brought to the new reference
+        auto settle = [&]() __attribute__((always_inline)) {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                l_run[mb] = l_run[mb] * corr[mb] + (sum0[mb] + sum1[mb]);
+                if (__builtin_amdgcn_ballot_w64(corr[mb] != 1.0f)) {
+#pragma unroll
+                    for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) accE[mb][hb][r] *= corr[mb];
+                }
+            }
+        };
+        // steady state (tiles i-1, i, i+1 all complete): one straight run, the steps of GEMM 2 of
+        // tile i-1, then those of GEMM 1 of tile i+1, a slice of the softmax of tile i behind each
+        auto steady = [&](auto curc, int i) __attribute__((always_inline)) {
+            constexpr int CUR = decltype(curc)::value;
+            set_d_slot(ring_off(i - 1));
+            set_b_slot(ring_off(i + 1));
+            v8 op[TT];
+            auto fetch = [&](auto tc) __attribute__((always_inline)) {
+                constexpr int t = decltype(tc)::value;
+                if constexpr (t < T2) op[t] = fetch_d(tc);
+                else op[t] = fetch_b(std::integral_constant<int, t - T2>{});
+            };
+            static_for<0, (PF < TT ? PF : TT)>([&](auto tc) { fetch(tc); });
+            static_for<0, TT>([&](auto tc) {
+                constexpr int t = decltype(tc)::value;
+                if constexpr (t + PF < TT) fetch(std::integral_constant<int, t + PF>{});
+                if constexpr (t < T2) g2_step(tc, op[t]);
+                else g1_step(std::integral_constant<int, t - T2>{}, std::integral_constant<int, CUR ^ 1>{}, op[t]);
+                vstep(tc, curc, std::false_type{}, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            settle();
+        };
+        // the softmax of tile t alone (first and last tiles; the last may be ragged, and a wave
+        // whose slice of it is empty contributes P = 0)
+        auto softmax_only = [&](auto curc, int t) __attribute__((always_inline)) {
+            const int n0 = t * TN + ncol0;
+            if (n0 < N) {
+                static_for<0, TT>([&](auto tc) { vstep(tc, curc, std::true_type{}, n0); });
+                settle();
+            } else {
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                        for (int qp = 0; qp < 2; ++qp)
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) pop[j][mb][qp][e] = (T)0.f;
+            }
+        };
+        int slot_l = PRE; // ring slot the next requested tile goes to
+        // top of iteration i: tile i+1 (if any) has landed, tile i+S-2 is requested
+        auto top = [&](int i) __attribute__((always_inline)) {
+            // at most the S-4 requests younger than tile i+1 may still be in flight
+            if (i + S - 3 <= n_iters - 1) wait_vm<(S - 4) * P>();
+            else wait_vm<0>();
+            __syncthreads(); // tile i+1 is complete for every wave; the slot of tile i-2 is free
+            if (i + S - 2 < n_iters) {
+                issue_tile(i + S - 2, slot_l);
+                slot_l = slot_l + 1 == S ? 0 : slot_l + 1;
+            }
+        };
+        if (n_iters > 0) {
+            const int last = n_iters - 1;
+            // tile 0 (requested in the prologue, like tiles 1 .. PRE-1): GEMM 1 alone
+            if (n_pre == PRE) wait_vm<(PRE - 1) * P>();
+            else wait_vm<0>();
+            __syncthreads();
+            g1_only(std::integral_constant<int, 0>{}, 0);
+            // iteration 0: no tile before it
+            top(0);
+            if (last >= 1) g1_only(std::integral_constant<int, 1>{}, 1);
+            softmax_only(std::integral_constant<int, 0>{}, 0);
+            // iterations 1 .. last-1: two per trip, the two C^T buffers swap roles at compile time
+            int i = 1;
+            for (; i + 1 <= last - 1; i += 2) {
+                top(i);
+                steady(std::integral_constant<int, 1>{}, i);
+                top(i + 1);
+                steady(std::integral_constant<int, 0>{}, i + 1);
+            }
+            if (i <= last - 1) {
+                top(i);
+                steady(std::integral_constant<int, 1>{}, i);
+                ++i;
+            }
+            // iteration `last` (if it is not iteration 0): GEMM 2 of the tile before, softmax of the last
+            if (last >= 1) {
+                top(last);
+                g2_only(last - 1);
+                if (last & 1) softmax_only(std::integral_constant<int, 1>{}, last);
+                else softmax_only(std::integral_constant<int, 0>{}, last);
+            }
+            // GEMM 2 of the last tile
+            g2_only(last);
         }
     } else if constexpr (!SKEW) {
         int stage_c = 0;     // ring slot of the tile being consumed
@@ -988,7 +1238,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
 // LDS bytes of an instantiation.
 template <int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool KSPLIT, int PD>
 constexpr int kernel_lds_bytes() {
-    constexpr int S = ring_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX, KSPLIT);
+    constexpr int S = ring_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX, KSPLIT, PD > 0 ? chain3_f_bytes(LD, PD) + 1024 : 0);
     if constexpr (PD > 0) return chain3_lds_bytes(KD, LD, PD, MB, RG, NS, NJ, S);
     else return total_lds_bytes(KD, LD, MB, RG, NS, NJ, S, KSPLIT);
 }

@@ -102,16 +102,26 @@ constexpr int pick_stages(int K, int L, int mb, int rg, int ns, int nj, int budg
 // blocks can share the 160 KiB LDS of a compute unit (measured: a deeper ring that costs the
 // second resident block loses more than it gains).
 constexpr int kLdsRingBudget = 80 * 1024;
-// Softmax chains in blocks of 8 waves run their two wave groups a phase apart, which keeps two
-// n-tiles live: their ring is at least 3 deep.
+// Softmax chains run a software pipeline over three consecutive n-tiles: in iteration i a wave
+// issues the MFMAs of GEMM 2 of tile i-1 and of GEMM 1 of tile i+1 with the softmax arithmetic of
+// tile i spread between them, so tiles i-1, i and i+1 are live and tile i+2 is landing: a ring of
+// 4 (measured: a deeper one is slower, by up to a fifth on the short attention shapes).
+// 0 = the arrangement cannot be pipelined because four stages do not fit the compute unit (its
+// softmax loop then runs the phases one after the other, see skewed_groups).  `extra` = LDS held
+// beside the ring (the F tile of a three-GEMM chain).
+constexpr int pipe_stages(int K, int L, int mb, int rg, int ns, int nj, bool softmax, bool ksplit = false, int extra = 0) {
+    if (!softmax || ksplit) return 0;
+    return total_lds_bytes(K, L, mb, rg, ns, nj, 4) + extra <= 160 * 1024 ? 4 : 0;
+}
+// Softmax chains that cannot be pipelined, in blocks of 8 waves, run their two wave groups a
+// phase apart, which keeps two n-tiles live: their ring is at least 3 deep.
 constexpr bool skewed_groups(int rg, int ns, bool softmax, bool ksplit = false) { return softmax && rg * ns == 8 && !ksplit; }
-constexpr int ring_stages(int K, int L, int mb, int rg, int ns, int nj, bool softmax, bool ksplit = false) {
-#ifdef MCF_FORCE_STAGES // experiments only
-    return MCF_FORCE_STAGES;
-#endif
+constexpr int ring_stages(int K, int L, int mb, int rg, int ns, int nj, bool softmax, bool ksplit = false, int extra = 0) {
     // the items of a k loop are small and many, and the shapes that need one rarely fill the
     // machine: as deep as the whole LDS allows, to keep as many loads in flight as possible
     if (ksplit) return pick_stages(K, L, mb, rg, ns, nj, 2 * kLdsRingBudget, true);
+    const int ps = pipe_stages(K, L, mb, rg, ns, nj, softmax, ksplit, extra);
+    if (ps) return ps;
     const int s = pick_stages(K, L, mb, rg, ns, nj, kLdsRingBudget);
     return (skewed_groups(rg, ns, softmax) && s < 3) ? 3 : s;
 }

@@ -35,7 +35,8 @@
 namespace mcf {
 
 int stages_for(const Variant *v) {
-    return ring_stages(v->K, v->L, v->mb, v->rg, v->ns, v->nj, v->softmax != 0, v->ksplit != 0);
+    return ring_stages(v->K, v->L, v->mb, v->rg, v->ns, v->nj, v->softmax != 0, v->ksplit != 0,
+                       v->P > 0 ? chain3_f_bytes(v->L, v->P) + 1024 : 0);
 }
 int lds_bytes_for(const Variant *v) {
     if (v->P > 0) return chain3_lds_bytes(v->K, v->L, v->P, v->mb, v->rg, v->ns, v->nj, stages_for(v));
@@ -44,7 +45,8 @@ int lds_bytes_for(const Variant *v) {
 
 // Registers per lane (eq. (1) restricted to the register-resident tiles, in 32-bit registers):
 // A tile (mb * K/16 operands of 4), E accumulators (mb * L/32 * 16), nj C accumulators and
-// their 16-bit copies per mb (16 + 8), the LDS operands in flight for one C tile (K/16 * 4 for
+// their 16-bit copies per mb (16 + 8; a pipelined softmax chain: two C tiles and the 16-bit
+// copies, 16 + 16 + 8), the LDS operands in flight for one C tile (K/16 * 4 for
 // B, L/32 * 8 for D), one load offset per wave-load of a stage, and a fixed allowance for
 // addresses and softmax state.  It tracks the compiler's allocation to within about 25 %;
 // the compiler's own numbers (scratch use) are the final arbiter, as PTX lowering is in
@@ -55,8 +57,12 @@ int vgpr_estimate(int K, int L, int mb, int rg, int ns, int nj, int softmax, int
     const int slot = ksplit ? ksplit_slot_bytes(K, L, mb, rg, 32 * ns * nj) : stage_bytes(K, L, 32 * ns * nj);
     const int loads = (ksplit ? 2 : 1) * ((slot / 1024 + rg * ns - 1) / (rg * ns));
     const int hb = h_blocks(L);
-    return mb * (K / 16) * 4 + mb * hb * 16 + nj * mb * (16 + 8) + (K / 16) * 4 + hb * 8 + loads + 24 +
-           (softmax ? 16 : 0);
+    // a pipelined softmax chain holds C of two consecutive n-tiles and the exponentials of one
+    // (and fetches its LDS operands two MFMA steps ahead instead of a GEMM at a time)
+    const bool piped = softmax && !ksplit;
+    const int c_tiles = piped ? nj * mb * (16 + 16 + 8) : nj * mb * (16 + 8);
+    const int operands = piped ? 16 : (K / 16) * 4 + hb * 8;
+    return mb * (K / 16) * 4 + mb * hb * 16 + c_tiles + operands + loads + 24 + (softmax ? 16 : 0);
 }
 
 // Registers a lane may use: the 512-entry file of a SIMD is shared by the waves resident on
