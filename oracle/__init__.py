@@ -7,4 +7,4 @@ It shares no code with the HIP path and never imports it.
   perf_model.py  the paper's tiling-expression traffic rules and analytical model, eq. (1)-(5)
   search.py      the paper's heuristic search over candidates, Alg. 1
 """
-from .chain import chain, chain_rows, chain3, intermediate_row, build_oracle  # noqa: F401
+from .chain import chain, chain_rows, chain3, chain_causal, intermediate_row, build_oracle  # noqa: F401

@@ -41,6 +41,8 @@ def _load():
         lib.mcf_oracle_intermediate_row.restype = None
         lib.mcf_oracle_chain3.argtypes = common + [i64, dp, ip, dp]
         lib.mcf_oracle_chain3.restype = ctypes.c_int
+        lib.mcf_oracle_chain_causal.argtypes = [i64] * 5 + [dp, ip, dp, ip, dp, ip, ctypes.c_double, i64, dp]
+        lib.mcf_oracle_chain_causal.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -123,3 +125,14 @@ def chain3(A, B, D, F, softmax=False, scale=1.0, return_threads=False):
                                         sf.ctypes.data_as(ip), G.ctypes.data_as(dp))
     del keep
     return (G, threads) if return_threads else G
+
+
+def chain_causal(A, B, D, scale=1.0, causal_offset=0):
+    """Softmax chain under a causal mask: row i sees the columns n <= i + causal_offset (a row
+    that sees none gives zeros).  float64 [b,M,L]."""
+    (b, M, K, N, L), args, keep = _prep(A, B, D)
+    E = np.zeros((b, M, L), dtype=np.float64)
+    _load().mcf_oracle_chain_causal(*args, float(scale), int(causal_offset),
+                                    E.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
+    del keep
+    return E

@@ -45,9 +45,14 @@ typedef struct {
     int64_t sa[3], sb[3], sd[3];
     int softmax;
     double scale;
+    int causal;             /* softmax only: row i sees the columns n <= i + causal_offset */
+    int64_t causal_offset;
 } chain_t;
 
-/* One output row E[b,i,0..L) into out[0..L); crow is scratch of N doubles. */
+/* One output row E[b,i,0..L) into out[0..L); crow is scratch of N doubles.
+ * With a causal mask (softmax only; not part of the paper: the usual attention convention) row i
+ * sees the columns n <= i + causal_offset only: the softmax runs over those columns, the others
+ * have P = 0, and a row that sees no column at all is a row of zeros. */
 static void chain_row(const chain_t *p, int64_t b, int64_t i, double *crow, double *out)
 {
     const double *Ab = p->A + b * p->sa[0] + i * p->sa[1];
@@ -62,18 +67,26 @@ static void chain_row(const chain_t *p, int64_t b, int64_t i, double *crow, doub
     }
 
     if (p->softmax) {
+        int64_t seen = p->N; /* columns this row sees */
+        if (p->causal) {
+            seen = i + p->causal_offset + 1;
+            if (seen < 0) seen = 0;
+            if (seen > p->N) seen = p->N;
+        }
         double mx = -INFINITY;
-        for (int64_t n = 0; n < p->N; ++n) {
+        for (int64_t n = 0; n < seen; ++n) {
             crow[n] *= p->scale;
             if (crow[n] > mx) mx = crow[n];
         }
         double den = 0.0;
-        for (int64_t n = 0; n < p->N; ++n) {
+        for (int64_t n = 0; n < seen; ++n) {
             crow[n] = exp(crow[n] - mx);
             den += crow[n];
         }
-        for (int64_t n = 0; n < p->N; ++n)
+        for (int64_t n = 0; n < seen; ++n)
             crow[n] /= den;
+        for (int64_t n = seen; n < p->N; ++n)
+            crow[n] = 0.0;
     }
 
     for (int64_t j = 0; j < p->L; ++j) {
@@ -92,6 +105,7 @@ static void fill(chain_t *p, int64_t batch, int64_t M, int64_t K, int64_t N, int
     p->A = A; p->B = B; p->D = D;
     for (int t = 0; t < 3; ++t) { p->sa[t] = sa[t]; p->sb[t] = sb[t]; p->sd[t] = sd[t]; }
     p->softmax = softmax; p->scale = scale;
+    p->causal = 0; p->causal_offset = 0;
 }
 
 /* Full tensor: E packed [batch, M, L].  Returns the number of threads used. */
@@ -193,6 +207,39 @@ int mcf_oracle_chain3(int64_t batch, int64_t M, int64_t K, int64_t N, int64_t L,
         }
         free(crow);
         free(erow);
+    }
+    return threads;
+}
+
+/*
+ * The softmax chain under a causal mask (not in the paper; the convention of attention
+ * kernels): row i of every batch sees the columns n <= i + causal_offset, i.e.
+ *   P[b,i,n] = exp(S[b,i,n] - max) / sum   over those n,   P = 0 elsewhere,
+ * with causal_offset = 0 the lower triangle and causal_offset = N - M the triangle aligned at
+ * the last row and column; a row that sees nothing gives E = 0.  E packed [batch, M, L].
+ */
+int mcf_oracle_chain_causal(int64_t batch, int64_t M, int64_t K, int64_t N, int64_t L,
+                            const double *A, const int64_t *sa, const double *B, const int64_t *sb,
+                            const double *D, const int64_t *sd, double scale, int64_t causal_offset,
+                            double *E)
+{
+    chain_t p;
+    fill(&p, batch, M, K, N, L, A, sa, B, sb, D, sd, 1, scale);
+    p.causal = 1;
+    p.causal_offset = causal_offset;
+    int threads = 1;
+    const int64_t rows = batch * M;
+#pragma omp parallel
+    {
+#ifdef _OPENMP
+#pragma omp single
+        threads = omp_get_num_threads();
+#endif
+        double *crow = (double *)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1));
+#pragma omp for schedule(static)
+        for (int64_t r = 0; r < rows; ++r)
+            chain_row(&p, r / M, r % M, crow, E + r * L);
+        free(crow);
     }
     return threads;
 }

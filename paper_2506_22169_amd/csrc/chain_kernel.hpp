@@ -39,22 +39,10 @@
 #include "mcf_geometry.h"
 #include "mcf_internal.h"
 
-// Hook for cycle-stamp instrumentation in experiments; expands to nothing in the library.
-#ifndef MCF_TRACE_POINT
-#define MCF_TRACE_POINT(id)
-#endif
-#ifndef MCF_PHASE
-#define MCF_PHASE_DECL
-#define MCF_PHASE(id)
-#define MCF_PHASE_DUMP
-#endif
-// Compile-time ablation mask for experiments (0 in the library): 1 no operand reads from LDS,
-// 2 no MFMA, 4 no combine, 8 no E store, 16 no barrier in the loop, 32 no loads in the loop.
+// The reference maximum of the online softmax follows the running row maximum only once that
+// has grown by more than this many binary orders of magnitude (0: always).
 #ifndef MCF_LAZY_MAX
 #define MCF_LAZY_MAX 8
-#endif
-#ifndef MCF_ABLATE
-#define MCF_ABLATE 0
 #endif
 
 namespace mcf {
@@ -205,7 +193,6 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     const int wave = uniform(tid >> 6);
     const int c = lane & 31, g = lane >> 5;
     const int wr = wave / NS, wn = wave % NS;
-    MCF_PHASE_DECL
 
     // Block index -> (batch, m-tile).  Consecutive hardware block ids go round-robin over the
     // 8 XCDs (each with its own L2); give every XCD a contiguous range of logical blocks so the
@@ -236,7 +223,6 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     const T *Dg = (const T *)p.D + batch * p.sd_b + ht * LD;
     T *Eg = (T *)p.E + batch * p.se_b + ht * LD;
 
-    MCF_TRACE_POINT(0);
     // ---- per-lane byte offsets of the B / D pieces this wave loads for every n-tile ----------
     // Wave-load j of a stage covers LDS bytes [1024 j, 1024 j + 1024): 16-byte slot 64 j + lane.
     // Slot -> (row, stored chunk); the global source is the logical chunk = stored ^ swizzle.
@@ -431,7 +417,6 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     } else {
         for (int t = 0; t < n_pre; ++t) issue_tile(t, t);
     }
-    MCF_TRACE_POINT(1);
 
     // ---- L_A: A tile (or chunk) in LDS -> registers, as the second MFMA operand A^T[k][m] ---
     // a_mode (softmax only: a negative or zero scale) as two masks, so that a kernel with a k
@@ -457,9 +442,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         // the A loads are older than the n_pre tile groups
         if (n_pre == PRE) wait_vm<PRE * P>();
         else wait_vm<0>();
-        MCF_TRACE_POINT(2);
         __syncthreads();
-        MCF_TRACE_POINT(3);
         load_a(A_LDS);
     }
 
@@ -499,7 +482,6 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             for (int r = 0; r < 16; ++r) accE[mb][hb][r] = 0.f;
     }
 
-    MCF_TRACE_POINT(4);
     // LDS -> register operand fetches.  The lane-dependent part of every address (row, swizzled
     // chunk) is computed once, here; per n-tile the ring slot's base is added (one VALU add per
     // distinct swizzle pattern), and everything else -- slice j, row steps -- is a compile-time
@@ -526,7 +508,6 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         }
     };
     auto load_b = [&](int j, int ks) __attribute__((always_inline)) -> v8 {
-        if (MCF_ABLATE & 1) return a[0][ks];
         if (BKC) {
             return __builtin_bit_cast(v8, *(const lds_u32x4 *)(smem + bb[ks] + 32 * j * RBB));
         } else {
@@ -537,7 +518,6 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         }
     };
     auto load_d = [&](int j, int hb, int qp) __attribute__((always_inline)) -> v8 {
-        if (MCF_ABLATE & 1) return a[0][(2 * hb + qp) % KS];
         const lds_u8 *src = smem + dd[hb] + (32 * j + 16 * qp) * RBD;
         i16x4 lo = lds_read_tr(src);
         i16x4 hi = lds_read_tr(src + 8 * RBD);
@@ -574,8 +554,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             if (t + PF < T1) bop[t + PF] = load_b((t + PF) / KS, (t + PF) % KS);
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
-                if (MCF_ABLATE & 2) accC[j][mb][ks] += (float)bop[t][0] * (float)a[mb][ks][1];
-                else accC[j][mb] = M_::run(bop[t], a[mb][ks], accC[j][mb]);
+                accC[j][mb] = M_::run(bop[t], a[mb][ks], accC[j][mb]);
             }
             __builtin_amdgcn_sched_barrier(0x406);
         }
@@ -648,8 +627,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             if (t + PF < T2) dop[t + PF] = load_d((t + PF) / (2 * HB), ((t + PF) / 2) % HB, (t + PF) % 2);
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
-                if (MCF_ABLATE & 2) accE[mb][hb][qp] += (float)dop[t][0] * (float)pop[j][mb][qp][1];
-                else accE[mb][hb] = M_::run(dop[t], pop[j][mb][qp], accE[mb][hb]);
+                accE[mb][hb] = M_::run(dop[t], pop[j][mb][qp], accE[mb][hb]);
             }
             __builtin_amdgcn_sched_barrier(0x406);
         }
@@ -670,7 +648,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             if (n_items - q >= S - 1) wait_vm<(S - 2) * P>();
             else wait_vm<0>();
             __syncthreads(); // item q is complete for every wave; the slot of item q-1 is free
-            if (q + S - 1 < n_items && !(MCF_ABLATE & 32)) {
+            if (q + S - 1 < n_items) {
                 issue_item(lt, lr, stage_l);
                 if (++lr == NI) { lr = 0; ++lt; }
                 stage_l = stage_l + 1 == S ? 0 : stage_l + 1;
@@ -679,7 +657,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             if (n0 < N) {
                 const unsigned st = stage_c * STAGE;
                 if (cr < KC) {
-                    if (!(MCF_ABLATE & 64)) load_a(st + A_LDS);
+                    load_a(st + A_LDS);
                     phase_g1(st, cr == 0);
                 } else {
                     phase_g2_prefetch(st);
@@ -934,24 +912,18 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             // state S-2 younger groups may stay in flight, near the end simply drain.
             if (n_iters - it >= S - 1) wait_vm<(S - 2) * P>();
             else wait_vm<0>();
-            MCF_TRACE_POINT(8 + 3 * (it & 7));
-            if (!(MCF_ABLATE & 16)) __syncthreads(); // tile `it` is complete for every wave; the slot of tile it-1 is free
-            if (it + S - 1 < n_iters && !(MCF_ABLATE & 32)) {
+            __syncthreads(); // tile `it` is complete for every wave; the slot of tile it-1 is free
+            if (it + S - 1 < n_iters) {
                 issue_tile(it + S - 1, stage_l);
                 stage_l = stage_l + 1 == S ? 0 : stage_l + 1;
             }
-            MCF_TRACE_POINT(9 + 3 * (it & 7));
             const int n0 = it * TN + wn * (32 * NJ); // first column of this wave's 32*NJ-wide slice
             if (n0 < N) {
                 const unsigned st = stage_c * STAGE;
-                MCF_PHASE(0);
                 phase_g1(st);
-                MCF_PHASE(1);
                 phase_g2_prefetch(st);
                 phase_sm(n0);
-                MCF_PHASE(2);
                 phase_g2();
-                MCF_PHASE(3);
             }
             stage_c = stage_c + 1 == S ? 0 : stage_c + 1;
         }
@@ -966,7 +938,6 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         static_assert(S >= 3, "the skewed loop keeps two tiles live");
         const int grp = wave >> 2;
         auto top = [&](int i) __attribute__((always_inline)) {
-            MCF_PHASE(0);
             if (i == 0) {
                 if (n_pre == S - 1) wait_vm<(S - 2) * P>();
                 else wait_vm<0>();
@@ -974,11 +945,8 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
                 if (i + S - 3 <= n_iters - 1) wait_vm<(S - 3) * P>();
                 else wait_vm<0>();
             }
-            MCF_PHASE(4);
             __syncthreads(); // tile i is complete for every wave; the slot of tile i-2 is free
-            MCF_PHASE(5);
             if (i >= 1 && i + S - 2 < n_iters) issue_tile(i + S - 2, (i + S - 2) % S);
-            MCF_PHASE(6);
         };
         const int ncol0 = wn * (32 * NJ);
         if (grp == 0) {
@@ -987,26 +955,19 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
                 const int n0 = i * TN + ncol0;
                 if (n0 < N) {
                     const unsigned st = (i % S) * STAGE;
-                    MCF_PHASE(0);
                     phase_g1(st);
-                    MCF_PHASE(1);
                     phase_g2_prefetch(st);
                     phase_sm(n0);
-                    MCF_PHASE(2);
                     phase_g2();
-                    MCF_PHASE(3);
                 }
             }
         } else {
             auto finish_tile = [&](int t) __attribute__((always_inline)) { // SM and G2 of tile t
                 const int n0 = t * TN + ncol0;
                 if (n0 < N) {
-                    MCF_PHASE(0);
                     phase_g2_prefetch((t % S) * STAGE);
                     phase_sm(n0);
-                    MCF_PHASE(2);
                     phase_g2();
-                    MCF_PHASE(3);
                 }
             };
             top(0);
@@ -1016,15 +977,12 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
                 finish_tile(i - 1);
                 if (i * TN + ncol0 < N) {
                     phase_g1((i % S) * STAGE);
-                    MCF_PHASE(1);
                 }
             }
             if (n_iters > 0) finish_tile(n_iters - 1);
         }
     }
 
-    MCF_PHASE_DUMP
-    MCF_TRACE_POINT(5);
     // ---- finish the softmax denominator -----------------------------------------------------
     if (SOFTMAX) {
 #pragma unroll
@@ -1097,10 +1055,9 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     // own (and its softmax state) in LDS, then reduces and stores the blocks it owns, so the
     // reduction and the store are spread over all waves.  Partial results are summed in wave
     // order, which makes the result independent of timing.
-    constexpr int NBLK = MB * HB;
     constexpr int BPW = blocks_per_wave(LD, MB, NS);
     const int blk0 = wn * BPW; // this wave owns blocks [blk0, blk0 + BPW) that exist
-    if (NS > 1 && !(MCF_ABLATE & 4)) {
+    if (NS > 1) {
         constexpr int PARK = parked_blocks(LD, MB, NS); // blocks a wave parks (those it does not own)
         constexpr int PER_W = PARK * 16 + 2 * MB;       // floats per lane per wave
         lds_f32 *scr = (lds_f32 *)smem + (wr * NS) * PER_W * 64 + lane;
@@ -1168,7 +1125,6 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         }
     }
 
-    MCF_TRACE_POINT(6);
     float inv[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) inv[mb] = SOFTMAX ? 1.0f / l_run[mb] : 1.0f;
@@ -1227,11 +1183,10 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             const int ch = (slot % CPR) ^ swz_b128(RBS, row);
             const u32x4 v = *(const lds_u32x4 *)(es + 16 * slot);
             if (EPAD && (ch >= 4 * HPW || 32 * h0 + 8 * ch >= LDX)) continue;
-            if (rbase + row < M && (!(MCF_ABLATE & 8) || v[0] == 0x12345u))
+            if (rbase + row < M)
                 __builtin_nontemporal_store(v, (u32x4 *)(Eg + (int64_t)(rbase + row) * se_r + 32 * h0 + 8 * ch));
         }
     }
-    MCF_TRACE_POINT(7);
 }
 
 // Host-side launcher of one instantiation.

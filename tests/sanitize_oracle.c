@@ -80,6 +80,21 @@ static int check_softmax_and_chain3(void)
                 if (fabs(s - E[(x * M + i) * L + j]) > 1e-14) bad = 1;
             }
         }
+    /* causal mask: every offset from "sees nothing" to "sees everything"; the row sums of what a
+     * row sees are checked through a D of ones */
+    {
+        double ones[b * N * L], Ec[b * M * L];
+        for (int i = 0; i < b * N * L; ++i) ones[i] = 1.0;
+        for (int off = -M - 1; off <= N + 1; ++off) {
+            mcf_oracle_chain_causal(b, M, K, N, L, A, sa, B, sb, ones, sd, 0.5, off, Ec);
+            for (int x = 0; x < b; ++x)
+                for (int i = 0; i < M; ++i)
+                    for (int j = 0; j < L; ++j) {
+                        const double want = (i + off >= 0) ? 1.0 : 0.0;
+                        if (fabs(Ec[(x * M + i) * L + j] - want) > 1e-14) bad = 1;
+                    }
+        }
+    }
     mcf_oracle_chain3(b, M, K, N, L, A, sa, B, sb, D, sd, 1, 0.5, P, F, sf, G);
     for (int x = 0; x < b; ++x)
         for (int i = 0; i < M; ++i)

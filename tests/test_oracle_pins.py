@@ -179,3 +179,45 @@ def test_chain3_bruteforce_and_identities():
     assert np.max(np.abs(got - ref)) <= 1e-12 * np.max(np.abs(ref))
     with pytest.raises(ValueError):
         oracle.chain3(A, B, D, np.zeros((b, L + 1, P)))
+
+
+def test_causal_mask_bruteforce_and_special_cases():
+    """The causal softmax chain (not in the paper; row i sees the columns n <= i + offset) against
+    a brute-force definition written here with an explicit mask, and against the cases that fix
+    the offset convention: the first row of the lower triangle is the first row of D, a mask that
+    hides nothing is the plain softmax chain, a row that sees k columns equals the chain over the
+    first k columns, a row that sees nothing is zero."""
+    rng = np.random.default_rng(31)
+    b, M, K, N, L = 2, 6, 3, 9, 4
+    A, B, D = rng.standard_normal((b, M, K)), rng.standard_normal((b, K, N)), rng.standard_normal((b, N, L))
+    scale = 0.7
+    for off in (0, 3, -2, N - M, N + 5, -M - 1):
+        E = oracle.chain_causal(A, B, D, scale=scale, causal_offset=off)
+        ref = np.zeros((b, M, L))
+        for bb in range(b):
+            for i in range(M):
+                cols = [n for n in range(N) if n <= i + off]
+                if not cols:
+                    continue
+                s = np.array([scale * sum(A[bb, i, k] * B[bb, k, n] for k in range(K)) for n in cols])
+                w = np.exp(s - s.max())
+                w /= w.sum()
+                for j in range(L):
+                    ref[bb, i, j] = sum(w[q] * D[bb, n, j] for q, n in enumerate(cols))
+        assert np.max(np.abs(E - ref)) <= 1e-14
+    low = oracle.chain_causal(A, B, D, scale=scale, causal_offset=0)
+    assert np.allclose(low[:, 0], D[:, 0], rtol=0, atol=1e-15)                    # one visible column: P = 1
+    full = oracle.chain(A, B, D, softmax=True, scale=scale)
+    assert np.array_equal(oracle.chain_causal(A, B, D, scale=scale, causal_offset=N - 1), full)
+    assert np.array_equal(oracle.chain_causal(A, B, D, scale=scale, causal_offset=N + 7), full)
+    for i in range(M):                                                            # row i sees i + 3 + 1 columns
+        k = min(N, i + 4)
+        part = oracle.chain(A[:, i:i + 1], B[:, :, :k], D[:, :k], softmax=True, scale=scale)
+        assert np.allclose(oracle.chain_causal(A, B, D, scale=scale, causal_offset=3)[:, i:i + 1], part, rtol=0, atol=1e-15)
+    hidden = oracle.chain_causal(A, B, D, scale=scale, causal_offset=-3)
+    assert not hidden[:, :3].any() and hidden[:, 3:].any()
+    # library special case: masked logits through scipy's softmax
+    C = scale * (A @ B)
+    C[:, np.arange(M)[:, None] + 2 < np.arange(N)[None, :]] = -np.inf
+    ref = scipy_softmax(C, axis=-1) @ D
+    assert np.max(np.abs(oracle.chain_causal(A, B, D, scale=scale, causal_offset=2) - ref)) <= 1e-14
