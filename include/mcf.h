@@ -28,7 +28,7 @@
 extern "C" {
 #endif
 
-typedef enum { MCF_F16 = 0, MCF_BF16 = 1 } mcf_dtype;
+typedef enum { MCF_F16 = 0, MCF_BF16 = 1, MCF_F32 = 2 /* output only */ } mcf_dtype;
 
 typedef enum {
     MCF_OK = 0,
@@ -53,7 +53,8 @@ typedef enum {
  * multiple of 128 with L in {64, 128, 256} through kernels with a k loop inside the block
  * (T_K = 128).  Any batch, M >= 0, N >= 0 (N >= 1 with softmax).  Other
  * (K, L) give MCF_EUNSUPPORTED.
- * in_dtype is the type of A, B, D; out_dtype that of E and must equal in_dtype.
+ * in_dtype is the type of A, B, D (MCF_F16 or MCF_BF16); out_dtype that of E: in_dtype, or
+ * MCF_F32 (the fp32 accumulators are then stored unrounded; e_stride counts fp32 elements).
  * Both GEMMs accumulate in fp32; C (or P) is rounded once to in_dtype between them.
  */
 typedef struct mcf_problem {
@@ -132,6 +133,19 @@ int mcf_gemm_chain(const mcf_problem *problem, const void *A, const void *B, con
 int mcf_softmax_gemm_chain(const mcf_problem *problem, float scale, const void *A,
                            const void *B, const void *D, void *E,
                            const mcf_tiles *tiles_or_null, void *hip_stream);
+
+/*
+ * The softmax chain under a causal mask (not in the paper; the convention of attention
+ * kernels): row i of every batch sees the columns n <= i + causal_offset only,
+ *     E[b,i,:] = softmax_{n <= i + causal_offset}(scale * A[b,i,:] . B[b,:,n]) . D[b,n,:],
+ * causal_offset = 0 being the lower triangle and causal_offset = N - M the triangle that ends
+ * in the last row and column; a row that sees no column is written as zeros.  n-tiles that no
+ * row of a block sees are neither loaded nor computed.  Everything else as
+ * mcf_softmax_gemm_chain (same kernels, same tile choice).
+ */
+int mcf_causal_softmax_gemm_chain(const mcf_problem *problem, float scale, int64_t causal_offset,
+                                  const void *A, const void *B, const void *D, void *E,
+                                  const mcf_tiles *tiles_or_null, void *hip_stream);
 
 /*
  * G = (E) . F with E the chain above, softmax != 0 selecting its softmax form (Sec. III-A: the

@@ -10,7 +10,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libmcf.so")
 _lib = None
 
-MCF_F16, MCF_BF16 = 0, 1
+MCF_F16, MCF_BF16, MCF_F32 = 0, 1, 2
 MCF_OK = 0
 
 
@@ -99,6 +99,8 @@ def load_library():
     lib.mcf_pick_tiles3.argtypes = [PP, ctypes.c_int64, ctypes.c_int, TP]
     lib.mcf_list_variants3.argtypes = [PP, ctypes.c_int64, ctypes.c_int, ctypes.POINTER(ctypes.c_int32), ctypes.c_int]
     lib.mcf_softmax_gemm_chain.argtypes = [PP, ctypes.c_float, vp, vp, vp, vp, TP, vp]
+    lib.mcf_causal_softmax_gemm_chain.argtypes = [PP, ctypes.c_float, ctypes.c_int64, vp, vp, vp, vp, TP, vp]
+    lib.mcf_causal_softmax_gemm_chain.restype = ctypes.c_int
     for f in (lib.mcf_pick_tiles, lib.mcf_eval_tiles, lib.mcf_list_variants, lib.mcf_gemm_chain,
               lib.mcf_softmax_gemm_chain, lib.mcf_search_tiles, lib.mcf_tune_tiles, lib.mcf_list_candidates,
               lib.mcf_gemm_chain3, lib.mcf_list_variants3, lib.mcf_pick_tiles3):
@@ -154,8 +156,9 @@ def _problem_from_tensors(A, B, D, E):
     b3, N2, L = D.shape
     if not (b == b2 == b3 and K == K2 and N == N2 and tuple(E.shape) == (b, M, L)):
         raise McfError(1, f"shape mismatch A{tuple(A.shape)} B{tuple(B.shape)} D{tuple(D.shape)} E{tuple(E.shape)}")
-    if not (A.dtype == B.dtype == D.dtype == E.dtype):
-        raise McfError(1, "A, B, D, E must share one dtype")
+    import torch
+    if not (A.dtype == B.dtype == D.dtype and E.dtype in (A.dtype, torch.float32)):
+        raise McfError(1, "A, B, D must share one dtype; E has that dtype or float32")
     if not (A.is_cuda and B.is_cuda and D.is_cuda and E.is_cuda):
         raise McfError(1, "A, B, D, E must be device tensors")
     if not (A.device == B.device == D.device == E.device):
@@ -177,7 +180,10 @@ def _problem_from_tensors(A, B, D, E):
         if shape[0] <= 1:
             s[0] = 0
         return s
-    return make_problem(b, M, K, N, L, code, st(A), st(B), st(D), st(E))
+    p = make_problem(b, M, K, N, L, code, st(A), st(B), st(D), st(E))
+    if E.dtype == torch.float32:
+        p.out_dtype = MCF_F32
+    return p
 
 
 def _stream_ptr(stream):
@@ -198,7 +204,7 @@ def _tiles_arg(tiles):
     return ctypes.byref(t)
 
 
-def _run(softmax, scale, A, B, D, out, tiles, stream):
+def _run(softmax, scale, A, B, D, out, tiles, stream, causal_offset=None):
     import torch
     lib = load_library()
     if out is None:
@@ -206,7 +212,9 @@ def _run(softmax, scale, A, B, D, out, tiles, stream):
     p = _problem_from_tensors(A, B, D, out)
     args = [ctypes.c_void_p(A.data_ptr()), ctypes.c_void_p(B.data_ptr()), ctypes.c_void_p(D.data_ptr()),
             ctypes.c_void_p(out.data_ptr()), _tiles_arg(tiles), _stream_ptr(stream)]
-    if softmax:
+    if causal_offset is not None:
+        _check(lib.mcf_causal_softmax_gemm_chain(ctypes.byref(p), ctypes.c_float(scale), ctypes.c_int64(int(causal_offset)), *args))
+    elif softmax:
         _check(lib.mcf_softmax_gemm_chain(ctypes.byref(p), ctypes.c_float(scale), *args))
     else:
         _check(lib.mcf_gemm_chain(ctypes.byref(p), *args))
@@ -223,6 +231,11 @@ def gemm_chain(A, B, D, out=None, tiles=None, stream=None):
 def softmax_gemm_chain(A, B, D, scale, out=None, tiles=None, stream=None):
     """mcf_softmax_gemm_chain: E = softmax_rows(scale * A . B) . D."""
     return _run(True, float(scale), A, B, D, out, tiles, stream)
+
+
+def causal_softmax_gemm_chain(A, B, D, scale, causal_offset=0, out=None, tiles=None, stream=None):
+    """mcf_causal_softmax_gemm_chain: the softmax chain with row i seeing the columns n <= i + causal_offset."""
+    return _run(True, float(scale), A, B, D, out, tiles, stream, causal_offset=causal_offset)
 
 
 def pick_tiles(problem, softmax=False):
@@ -319,11 +332,13 @@ def gemm_chain3(A, B, D, F, scale=None, out=None, tiles=None, stream=None):
     P = F.shape[2]
     if out is None:
         out = torch.empty((A.shape[0], A.shape[1], P), dtype=A.dtype, device=A.device)
-    if tuple(out.shape) != (A.shape[0], A.shape[1], P) or not (out.dtype == F.dtype == A.dtype) or out.device != A.device \
-            or F.device != A.device:
+    if tuple(out.shape) != (A.shape[0], A.shape[1], P) or not (F.dtype == A.dtype and out.dtype in (A.dtype, torch.float32)) \
+            or out.device != A.device or F.device != A.device:
         raise McfError(1, "F and the output must match A in dtype and device, the output be [b, M, P]")
     # A, B, D as in the two-GEMM chain (a stand-in E of the right shape carries no strides)
     p = _problem_from_tensors(A, B, D, _MetaLike(A, D))
+    if out.dtype == torch.float32:
+        p.out_dtype = MCF_F32
     so = list(out.stride()) if out.numel() else [0, 0, 0]
     if out.shape[0] <= 1:
         so[0] = 0

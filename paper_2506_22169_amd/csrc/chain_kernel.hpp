@@ -32,6 +32,7 @@
 // the ns waves of a row-group are combined through LDS after the loop.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 #include <type_traits>
@@ -48,6 +49,7 @@
 namespace mcf {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short i16x4 __attribute__((ext_vector_type(4)));
@@ -255,8 +257,26 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     };
     unsigned voff[P]; // filled after the A tile has been requested: the first load leaves as early as possible
 
-    const int n_iters = (N + TN - 1) / TN;
-    const int n_full = N / TN; // tiles [0, n_full) are complete, tile n_full (if any) is ragged
+    // Causal mask (softmax chains only): row i sees the columns n <= i + causal_off, so a block
+    // visits the columns its last row sees (NV), a wave has work in a tile while the tile starts
+    // below what the wave's last row sees (n_wave), a tile needs no masking for a wave while it
+    // ends at or below what the wave's first row sees (n_clean), and a lane masks the columns
+    // from lim[mb] on.  Without a mask all of these are N.
+    const bool causal = SOFTMAX && p.causal != 0;
+    const int causal_off = p.causal_off;
+    auto sees = [&](int row) __attribute__((always_inline)) { // columns row `row` sees, 0 .. N
+        const int v = row + causal_off + 1;
+        return causal ? (v < 0 ? 0 : (v > N ? N : v)) : N;
+    };
+    const int wrow0 = mrow0 + wr * (32 * MB); // first row of this wave
+    const int NV = sees((mrow0 + TM < M ? mrow0 + TM : M) - 1);
+    const int n_wave = sees((wrow0 + 32 * MB < M ? wrow0 + 32 * MB : M) - 1);
+    const int n_clean = sees(wrow0);
+    int lim[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) lim[mb] = sees(wrow0 + 32 * mb + c);
+    const int n_iters = (NV + TN - 1) / TN;
+    const int n_full = N / TN; // tiles [0, n_full) are complete in memory, tile n_full (if any) is ragged
 
     auto issue_tile = [&](int t, int stage) __attribute__((always_inline)) {
         const int nt0 = t * TN;
@@ -571,12 +591,12 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     auto phase_sm = [&](int n0) __attribute__((always_inline)) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-            if (n0 + 32 * NJ > N) { // ragged last tile: columns past N contribute nothing
+            if (n0 + 32 * NJ > n_clean) { // ragged last tile, or a tile on the mask's edge: columns a row does not see contribute nothing
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
-                        if (n0 + 32 * j + 8 * (r / 4) + 4 * g + (r % 4) >= N) accC[j][mb][r] = SOFTMAX ? -INFINITY : 0.f;
+                        if (n0 + 32 * j + 8 * (r / 4) + 4 * g + (r % 4) >= lim[mb]) accC[j][mb][r] = SOFTMAX ? -INFINITY : 0.f;
             }
             if (SOFTMAX) {
                 float mx = accC[0][mb][0];
@@ -592,8 +612,10 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
                 // result is the same up to rounding: numerator and denominator share m.
                 float m_new = fmaxf(m_run[mb], mx);
                 if (MCF_LAZY_MAX > 0) m_new = (m_new - m_run[mb]) * c1 > (float)MCF_LAZY_MAX ? m_new : m_run[mb];
-                const float corr = __builtin_amdgcn_exp2f((m_run[mb] - m_new) * c1);
-                const float mneg = -m_new * c1;
+                // a row that has seen no column yet (under a mask) keeps m = -inf: p = 0, nothing to rescale
+                const bool blind = m_new == -INFINITY;
+                const float corr = blind ? 1.0f : __builtin_amdgcn_exp2f((m_run[mb] - m_new) * c1);
+                const float mneg = blind ? 0.f : -m_new * c1;
                 float sum = 0.f;
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
@@ -654,7 +676,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
                 stage_l = stage_l + 1 == S ? 0 : stage_l + 1;
             }
             const int n0 = ct * TN + wn * (32 * NJ);
-            if (n0 < N) {
+            if (n0 < n_wave) {
                 const unsigned st = stage_c * STAGE;
                 if (cr < KC) {
                     load_a(st + A_LDS);
@@ -701,10 +723,10 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             for (int mb = 0; mb < MB; ++mb) {
                 if constexpr (k < TA) {
                     if constexpr (k == 0) {
-                        if (MAY_BE_RAGGED && n0 + 32 * NJ > N) { // ragged last tile: columns past N contribute nothing
+                        if (MAY_BE_RAGGED && n0 + 32 * NJ > n_clean) { // ragged last tile or the mask's edge: columns a row does not see contribute nothing
 #pragma unroll
                             for (int e = 0; e < NE; ++e)
-                                if (n0 + 32 * (e / 16) + 8 * ((e % 16) / 4) + 4 * g + (e % 4) >= N) cc[CUR][e / 16][mb][e % 16] = -INFINITY;
+                                if (n0 + 32 * (e / 16) + 8 * ((e % 16) / 4) + 4 * g + (e % 4) >= lim[mb]) cc[CUR][e / 16][mb][e % 16] = -INFINITY;
                         }
                         mx[mb] = cc[CUR][0][mb][0];
                     }
@@ -715,8 +737,10 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
                         const float m_row = xhalf_max(mx[mb]);
                         float m_new = fmaxf(m_run[mb], m_row);
                         if (MCF_LAZY_MAX > 0) m_new = (m_new - m_run[mb]) * c1 > (float)MCF_LAZY_MAX ? m_new : m_run[mb];
-                        corr[mb] = __builtin_amdgcn_exp2f((m_run[mb] - m_new) * c1);
-                        mneg[mb] = -m_new * c1;
+                        // (under a mask) a row that has seen no column yet keeps m = -inf: p = 0, nothing to rescale
+                        const bool blind = MAY_BE_RAGGED && m_new == -INFINITY;
+                        corr[mb] = blind ? 1.0f : __builtin_amdgcn_exp2f((m_run[mb] - m_new) * c1);
+                        mneg[mb] = blind ? 0.f : -m_new * c1;
                         pin(mneg[mb]);
                         pin(corr[mb]);
                         m_run[mb] = m_new;
@@ -844,7 +868,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         // whose slice of it is empty contributes P = 0)
         auto softmax_only = [&](auto curc, int t) __attribute__((always_inline)) {
             const int n0 = t * TN + ncol0;
-            if (n0 < N) {
+            if (n0 < n_wave) {
                 static_for<0, TT>([&](auto tc) { vstep(tc, curc, std::true_type{}, n0); });
                 settle();
             } else {
@@ -881,25 +905,43 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             top(0);
             if (last >= 1) g1_only(std::integral_constant<int, 1>{}, 1);
             softmax_only(std::integral_constant<int, 0>{}, 0);
-            // iterations 1 .. last-1: two per trip, the two C^T buffers swap roles at compile time
+            // iterations 1 .. last-1.  Those whose tile needs no masking for this wave (all of them
+            // without a causal mask; the tiles left of the mask's edge with one) run the steady
+            // state, two per trip so that the two C^T buffers swap roles at compile time ...
+            int steady_end = (n_clean - ncol0 - 32 * NJ) / TN; // last tile that ends at or below n_clean
+            if (n_clean - ncol0 - 32 * NJ < 0) steady_end = -1;
+            if (steady_end > last - 1) steady_end = last - 1;
             int i = 1;
-            for (; i + 1 <= last - 1; i += 2) {
+            for (; i + 1 <= steady_end; i += 2) {
                 top(i);
                 steady(std::integral_constant<int, 1>{}, i);
                 top(i + 1);
                 steady(std::integral_constant<int, 0>{}, i + 1);
             }
-            if (i <= last - 1) {
+            if (i <= steady_end) {
                 top(i);
                 steady(std::integral_constant<int, 1>{}, i);
                 ++i;
             }
-            // iteration `last` (if it is not iteration 0): GEMM 2 of the tile before, softmax of the last
-            if (last >= 1) {
-                top(last);
-                g2_only(last - 1);
-                if (last & 1) softmax_only(std::integral_constant<int, 1>{}, last);
-                else softmax_only(std::integral_constant<int, 0>{}, last);
+            // ... and the rest the parts one after the other: the tiles on the mask's edge, and the
+            // last tile (GEMM 2 of the tile before it, its softmax, no tile after it).  From here on
+            // the tile in the softmax always sits in the first C^T buffer (copied there: a branch on
+            // the parity of i in this tail would keep both buffers and their copies alive all along).
+            auto first_from_second = [&]() __attribute__((always_inline)) {
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) cc[0][j][mb] = cc[1][j][mb];
+            };
+            if (i <= last && (i & 1)) first_from_second();
+            for (; i <= last; ++i) {
+                top(i);
+                g2_only(i - 1);
+                softmax_only(std::integral_constant<int, 0>{}, i);
+                if (i < last) {
+                    g1_only(std::integral_constant<int, 1>{}, i + 1);
+                    first_from_second();
+                }
             }
             // GEMM 2 of the last tile
             g2_only(last);
@@ -918,7 +960,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
                 stage_l = stage_l + 1 == S ? 0 : stage_l + 1;
             }
             const int n0 = it * TN + wn * (32 * NJ); // first column of this wave's 32*NJ-wide slice
-            if (n0 < N) {
+            if (n0 < n_wave) {
                 const unsigned st = stage_c * STAGE;
                 phase_g1(st);
                 phase_g2_prefetch(st);
@@ -953,7 +995,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             for (int i = 0; i < n_iters; ++i) {
                 top(i);
                 const int n0 = i * TN + ncol0;
-                if (n0 < N) {
+                if (n0 < n_wave) {
                     const unsigned st = (i % S) * STAGE;
                     phase_g1(st);
                     phase_g2_prefetch(st);
@@ -964,18 +1006,18 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         } else {
             auto finish_tile = [&](int t) __attribute__((always_inline)) { // SM and G2 of tile t
                 const int n0 = t * TN + ncol0;
-                if (n0 < N) {
+                if (n0 < n_wave) {
                     phase_g2_prefetch((t % S) * STAGE);
                     phase_sm(n0);
                     phase_g2();
                 }
             };
             top(0);
-            if (ncol0 < N) phase_g1(0);
+            if (ncol0 < n_wave) phase_g1(0);
             for (int i = 1; i < n_iters; ++i) {
                 top(i);
                 finish_tile(i - 1);
-                if (i * TN + ncol0 < N) {
+                if (i * TN + ncol0 < n_wave) {
                     phase_g1((i % S) * STAGE);
                 }
             }
@@ -1127,7 +1169,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
 
     float inv[MB];
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) inv[mb] = SOFTMAX ? 1.0f / l_run[mb] : 1.0f;
+    for (int mb = 0; mb < MB; ++mb) inv[mb] = SOFTMAX ? (l_run[mb] > 0.f ? 1.0f / l_run[mb] : 0.f) : 1.0f; // (a row that saw no column: zeros)
 
     // ---- S_E: output tile -> global ---------------------------------------------------------
     // Lane (c,g) holds X[row c][32hb + 16g + 0..15] of the blocks its wave owns (X = E, or the
@@ -1139,7 +1181,34 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     constexpr int HBX = h_blocks(LDX);
     constexpr int BPWX = blocks_per_wave(LDX, MB, NS);
     const int blk0x = wn * BPWX; // this wave owns blocks [blk0x, blk0x + BPWX) that exist
-    if (blk0x < MB * HBX) {
+    // fp32 output (bit 0 of the output pointer, which is 16-byte aligned, says so: a flag of its
+    // own would occupy a scalar register from the first instruction to here): the accumulators go
+    // out as they are held, 16 consecutive columns of a row per lane in four 16-byte stores
+    const bool out_f32 = ((uintptr_t)p.E & 1) != 0;
+    if (out_f32) {
+        float *Ef = (float *)((uintptr_t)p.E & ~(uintptr_t)15) + batch * p.se_b + ht * LD;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            const int row = wrow0 + 32 * mb + c;
+#pragma unroll
+            for (int hb = 0; hb < HBX; ++hb) {
+                const int blk = mb * HBX + hb;
+                if (blk >= blk0x && blk < blk0x + BPWX && row < M) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        f32x4 v;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            if constexpr (CH3 && NS == 1) v[e] = accO[mb][hb][4 * q + e];
+                            else v[e] = accE[mb][hb][4 * q + e] * inv[mb];
+                        }
+                        const int col = 32 * hb + 16 * g + 4 * q;
+                        if (col < LDX) __builtin_nontemporal_store(v, (f32x4 *)(Ef + (int64_t)row * se_r + col));
+                    }
+                }
+            }
+        }
+    } else if (blk0x < MB * HBX) {
         static_assert(combine_runs_ok(LDX, MB, NS), "a wave's run of blocks straddles row sets");
         constexpr int HPW = BPWX < HBX ? BPWX : HBX;     // h blocks per owned row set
         constexpr int MPW = BPWX < HBX ? 1 : BPWX / HBX; // row sets (of 32 rows) owned

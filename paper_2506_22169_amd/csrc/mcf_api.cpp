@@ -35,7 +35,7 @@ static bool span_fits(int64_t batch, int64_t rows, int64_t cols, const int64_t s
 
 int decode_layout(const mcf_problem *p, Layout *o) {
     if (p->in_dtype != MCF_F16 && p->in_dtype != MCF_BF16) return MCF_EUNSUPPORTED;
-    if (p->out_dtype != p->in_dtype) return MCF_EUNSUPPORTED;
+    if (p->out_dtype != p->in_dtype && p->out_dtype != MCF_F32) return MCF_EUNSUPPORTED;
     {
         int tk = 0, ksplit = 0;
         if (p->K > 65536 || p->L > 4096 || !resolve_group(p->in_dtype, p->K, p->L, &tk, &ksplit)) return MCF_EUNSUPPORTED;
@@ -87,9 +87,10 @@ static int64_t span(int64_t batch, int64_t rows, int64_t cols, const int64_t s[3
     return 1 + (batch - 1) * s[0] + (rows - 1) * s[1] + (cols - 1) * s[2];
 }
 
-static bool overlaps(const void *x, int64_t xe, const void *y, int64_t ye) {
+// x: xe elements of xs bytes; y: ye elements of 2 bytes
+static bool overlaps(const void *x, int64_t xe, int64_t xs, const void *y, int64_t ye) {
     const char *a = (const char *)x, *b = (const char *)y;
-    return xe > 0 && ye > 0 && a < b + 2 * ye && b < a + 2 * xe;
+    return xe > 0 && ye > 0 && a < b + 2 * ye && b < a + xs * xe;
 }
 
 // Variant of the three-GEMM chain for (dtype, K, L, P) and an arrangement, or nullptr.
@@ -130,7 +131,7 @@ static int pick3(const mcf_problem *p, int softmax, int b_kcontig, int64_t P, mc
 // strides fstr (all zero = packed), and E / e_stride describe the output [b, M, P].
 static int run(const mcf_problem *p_in, int softmax, float scale, const void *A, const void *B, const void *D, void *E,
                const mcf_tiles *tiles, void *stream, int64_t P = 0, const int64_t *fstr = nullptr,
-               const void *F = nullptr) {
+               const void *F = nullptr, bool causal = false, int64_t causal_off = 0) {
     set_last_error("");
     if (!p_in) return MCF_EINVAL;
     mcf_problem pc = *p_in;
@@ -166,7 +167,8 @@ static int run(const mcf_problem *p_in, int softmax, float scale, const void *A,
     const int64_t ea = span(p->batch, p->M, p->K, lay.sa), eb = span(p->batch, p->K, p->N, lay.sb);
     const int64_t ed = span(p->batch, p->N, p->L, lay.sd), ee = span(p->batch, p->M, ch3 ? P : p->L, lay.se);
     const int64_t ef = ch3 ? span(p->batch, p->L, P, sf) : 0;
-    if (overlaps(E, ee, A, ea) || overlaps(E, ee, B, eb) || overlaps(E, ee, D, ed) || (ch3 && overlaps(E, ee, F, ef)))
+    const int64_t es = p->out_dtype == MCF_F32 ? 4 : 2; // bytes per element of the output
+    if (overlaps(E, ee, es, A, ea) || overlaps(E, ee, es, B, eb) || overlaps(E, ee, es, D, ed) || (ch3 && overlaps(E, ee, es, F, ef)))
         return MCF_EINVAL;
     const uintptr_t ptrs[5] = {(uintptr_t)A, (uintptr_t)B, (uintptr_t)D, (uintptr_t)E, (uintptr_t)F};
     for (int t = 0; t < 5; ++t)
@@ -214,6 +216,13 @@ static int run(const mcf_problem *p_in, int softmax, float scale, const void *A,
     k.c1 = 1.0f; k.a_mode = 0;
     k.k_chunks = (int32_t)(p->K / v->K);
     k.F = F; k.sf_b = sf[0]; k.sf_r = sf[1];
+    if (p->out_dtype == MCF_F32) k.E = (void *)((uintptr_t)E | 1); // the kernels read bit 0 as "store fp32"
+    if (causal && causal_off < p->N - 1) { // (an offset of N - 1 or more hides nothing)
+        // the kernel forms row + offset + 1 in 32 bits
+        if (p->M + p->N >= (1ll << 31) - 1024) return MCF_EUNSUPPORTED;
+        k.causal = 1;
+        k.causal_off = (int32_t)(causal_off < -p->M - 1 ? -p->M - 1 : causal_off); // below -M nothing is seen either
+    }
     if (softmax) {
         // exp(scale*s - max) = exp2(|scale|*log2(e) * (s' - max')) with s' = +-s; a zero scale
         // makes every logit equal, which is what A := 0 gives.
@@ -239,6 +248,11 @@ extern "C" int mcf_gemm_chain(const mcf_problem *p, const void *A, const void *B
 extern "C" int mcf_softmax_gemm_chain(const mcf_problem *p, float scale, const void *A, const void *B, const void *D,
                                       void *E, const mcf_tiles *tiles, void *stream) {
     return mcf::run(p, 1, scale, A, B, D, E, tiles, stream);
+}
+
+extern "C" int mcf_causal_softmax_gemm_chain(const mcf_problem *p, float scale, int64_t causal_offset, const void *A,
+                                             const void *B, const void *D, void *E, const mcf_tiles *tiles, void *stream) {
+    return mcf::run(p, 1, scale, A, B, D, E, tiles, stream, 0, nullptr, nullptr, true, causal_offset);
 }
 
 extern "C" int mcf_gemm_chain3(const mcf_problem *p, int softmax, float scale, int64_t P, const int64_t *f_stride,

@@ -33,8 +33,10 @@ struct KParams {
     int32_t a_mode;     // 0: A as is, 1: -A (negative scale), 2: A := 0 (scale == 0)
     int32_t k_chunks;   // kernels with a k loop: K / T_K (otherwise unused)
     float c1;           // |scale| * log2(e) (softmax only)
+    int32_t causal;     // softmax only: 1 = row i sees the columns n <= i + causal_off
+    int32_t causal_off;
     const void *A, *B, *D;
-    void *E;
+    void *E;            // bit 0 set: written as fp32 (the pointer itself is 16-byte aligned; strides then count fp32 elements)
     int64_t sa_b, sa_r; // A: batch / row stride (col stride 1)
     int64_t sb_b, sb_r; // B: batch stride / stride of the non-contiguous index
     int64_t sd_b, sd_r; // D: batch / row stride

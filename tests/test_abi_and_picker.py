@@ -63,6 +63,16 @@ def test_validation_codes_without_a_launch():
     assert call(p, [ctypes.c_void_p(4096 + 2)] + fake[1:]) == 3                          # misaligned pointer
     assert call(p, [fake[3]] + fake[1:]) == 1                                            # E aliases A
     assert call(p, [None] + fake[1:]) == 1                                               # null pointer
+    bad_out = make_problem(2, 64, 64, 64, 64, "f16")
+    bad_out.out_dtype = 1                                                                # bf16 out of f16 in
+    assert call(bad_out) == 2
+    bad_out.in_dtype, bad_out.out_dtype = 2, 2                                           # fp32 inputs
+    assert call(bad_out) == 2
+    f32_out = make_problem(2, 64, 64, 64, 64, "f16")
+    f32_out.out_dtype = 2                                                                # fp32 out: a layout the picker accepts
+    assert pick(f32_out) == 0
+    assert lib.mcf_causal_softmax_gemm_chain(ctypes.byref(make_problem(2, 64, 64, 0, 64, "f16")), ctypes.c_float(1.0),
+                                             ctypes.c_int64(0), *fake, None, None) == 1   # softmax over nothing
     assert call(make_problem(0, 64, 64, 64, 64, "f16")) == 0                             # empty: no-op
     assert lib.mcf_softmax_gemm_chain(ctypes.byref(make_problem(2, 64, 64, 0, 64, "f16")), ctypes.c_float(1.0),
                                       *fake, None, None) == 1                            # softmax over nothing
