@@ -82,7 +82,9 @@ typedef struct mcf_tiles {
     int32_t lds_bytes;        /* eq. (1) restricted to the tiles held in LDS (B, D; x stages)    */
     int32_t vgpr_est;         /* eq. (1) restricted to the tiles held in registers (A, C, E)     */
     int32_t vgpr_used;        /* registers per lane the compiler allocated for this variant      */
-    int32_t scratch_bytes;    /* per-lane spill space of the variant (non-zero: never picked)    */
+    int32_t scratch_bytes;    /* per-lane spill space of a variant whose loops spill registers   *
+                               * (non-zero: never picked); registers only parked in scratch      *
+                               * across the n loop, outside of it, are not counted               */
     int64_t blocks;           /* N_block of eq. (5)                                              */
     int64_t compulsory_bytes; /* A, B, D read once + E written once                              */
     int64_t model_bytes;      /* numerator of eq. (3): sum of tile bytes x trip counts           */

@@ -137,8 +137,16 @@ template <int N> static __device__ __forceinline__ void wait_vm() {
 // PD > 0: chain of three GEMMs.  After the n loop the block multiplies its E tile (still in
 // registers) by F[L x PD], which waits in LDS from the prologue on, and stores that product
 // instead of E.  The rows of E must then be complete within a wave: NS = 1.
+// Waves per SIMD the compiler is to leave room for (pipelined softmax kernels that can have two
+// blocks resident; everything else: what the block size itself implies).
+template <int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool KSPLIT, int PD> constexpr int waves_per_simd() {
+    constexpr int extra = PD > 0 ? chain3_f_bytes(LD, PD) + 1024 : 0;
+    if (pipe_stages(KD, LD, MB, RG, NS, NJ, SOFTMAX, KSPLIT, extra) > 0) return pipe_waves_per_simd(KD, LD, MB, RG, NS, NJ, extra);
+    return RG * NS >= 4 ? RG * NS / 4 : 1;
+}
 template <typename T, int KD, int LD, int MB, int RG, int NS, int NJ, bool SOFTMAX, bool BKC, bool KSPLIT = false, int PD = 0>
-__global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
+__global__ __launch_bounds__(64 * RG * NS) __attribute__((amdgpu_waves_per_eu(waves_per_simd<KD, LD, MB, RG, NS, NJ, SOFTMAX, KSPLIT, PD>())))
+void chain_kernel(const KParams p) {
     using M_ = Mfma<T>;
     using v8 = typename M_::v8;
     constexpr int W = RG * NS;           // waves per block
@@ -258,23 +266,19 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     unsigned voff[P]; // filled after the A tile has been requested: the first load leaves as early as possible
 
     // Causal mask (softmax chains only): row i sees the columns n <= i + causal_off, so a block
-    // visits the columns its last row sees (NV), a wave has work in a tile while the tile starts
-    // below what the wave's last row sees (n_wave), a tile needs no masking for a wave while it
-    // ends at or below what the wave's first row sees (n_clean), and a lane masks the columns
-    // from lim[mb] on.  Without a mask all of these are N.
-    const bool causal = SOFTMAX && p.causal != 0;
+    // visits the columns its last row sees (NV), and a tile needs no masking for a wave while it
+    // ends at or below what the wave's first row sees (n_clean); in the other tiles a lane masks
+    // the columns its row does not see, which may be all of them.  Without a mask (causal_off =
+    // N - 1) both are N.
     const int causal_off = p.causal_off;
     auto sees = [&](int row) __attribute__((always_inline)) { // columns row `row` sees, 0 .. N
+        if constexpr (!SOFTMAX) return N;
         const int v = row + causal_off + 1;
-        return causal ? (v < 0 ? 0 : (v > N ? N : v)) : N;
+        return v < 0 ? 0 : (v > N ? N : v);
     };
     const int wrow0 = mrow0 + wr * (32 * MB); // first row of this wave
     const int NV = sees((mrow0 + TM < M ? mrow0 + TM : M) - 1);
-    const int n_wave = sees((wrow0 + 32 * MB < M ? wrow0 + 32 * MB : M) - 1);
     const int n_clean = sees(wrow0);
-    int lim[MB];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) lim[mb] = sees(wrow0 + 32 * mb + c);
     const int n_iters = (NV + TN - 1) / TN;
     const int n_full = N / TN; // tiles [0, n_full) are complete in memory, tile n_full (if any) is ragged
 
@@ -592,11 +596,12 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             if (n0 + 32 * NJ > n_clean) { // ragged last tile, or a tile on the mask's edge: columns a row does not see contribute nothing
+                const int lim = sees(wrow0 + 32 * mb + c);
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
-                        if (n0 + 32 * j + 8 * (r / 4) + 4 * g + (r % 4) >= lim[mb]) accC[j][mb][r] = SOFTMAX ? -INFINITY : 0.f;
+                        if (n0 + 32 * j + 8 * (r / 4) + 4 * g + (r % 4) >= lim) accC[j][mb][r] = SOFTMAX ? -INFINITY : 0.f;
             }
             if (SOFTMAX) {
                 float mx = accC[0][mb][0];
@@ -676,7 +681,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
                 stage_l = stage_l + 1 == S ? 0 : stage_l + 1;
             }
             const int n0 = ct * TN + wn * (32 * NJ);
-            if (n0 < n_wave) {
+            if (n0 < N) {
                 const unsigned st = stage_c * STAGE;
                 if (cr < KC) {
                     load_a(st + A_LDS);
@@ -716,17 +721,27 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         float mx[MB], mneg[MB], corr[MB], sum0[MB], sum1[MB];
 
         // element e of a row set <-> slice j = e / 16, accumulator register r = e % 16
-        auto vstep = [&](auto kc, auto curc, auto raggedc, int n0) __attribute__((always_inline)) {
+        auto vstep = [&](auto kc, auto curc, int n0) __attribute__((always_inline)) {
             constexpr int k = decltype(kc)::value, CUR = decltype(curc)::value;
-            constexpr bool MAY_BE_RAGGED = decltype(raggedc)::value;
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
                 if constexpr (k < TA) {
                     if constexpr (k == 0) {
-                        if (MAY_BE_RAGGED && n0 + 32 * NJ > n_clean) { // ragged last tile or the mask's edge: columns a row does not see contribute nothing
+                        // a ragged last tile, or a tile on or beyond the mask's edge: columns a row does
+                        // not see contribute nothing (tiles before the last are whole in memory, so
+                        // without a mask the test only ever holds for the last)
+                        if (n0 + 32 * NJ > n_clean) {
+                            // element e sits 32(e/16) + 8((e%16)/4) + e%4 columns right of the lane's first;
+                            // one compare and one select per element, in order (the pin keeps the
+                            // compiler from forming all the compares first, a scalar register pair each)
+                            const int room = sees(wrow0 + 32 * mb + c) - n0 - 4 * g; // columns the row sees from there on
 #pragma unroll
-                            for (int e = 0; e < NE; ++e)
-                                if (n0 + 32 * (e / 16) + 8 * ((e % 16) / 4) + 4 * g + (e % 4) >= lim[mb]) cc[CUR][e / 16][mb][e % 16] = -INFINITY;
+                            for (int e = 0; e < NE; ++e) {
+                                float x = cc[CUR][e / 16][mb][e % 16];
+                                x = 32 * (e / 16) + 8 * ((e % 16) / 4) + (e % 4) < room ? x : -INFINITY;
+                                pin(x);
+                                cc[CUR][e / 16][mb][e % 16] = x;
+                            }
                         }
                         mx[mb] = cc[CUR][0][mb][0];
                     }
@@ -738,7 +753,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
                         float m_new = fmaxf(m_run[mb], m_row);
                         if (MCF_LAZY_MAX > 0) m_new = (m_new - m_run[mb]) * c1 > (float)MCF_LAZY_MAX ? m_new : m_run[mb];
                         // (under a mask) a row that has seen no column yet keeps m = -inf: p = 0, nothing to rescale
-                        const bool blind = MAY_BE_RAGGED && m_new == -INFINITY;
+                        const bool blind = m_new == -INFINITY;
                         corr[mb] = blind ? 1.0f : __builtin_amdgcn_exp2f((m_run[mb] - m_new) * c1);
                         mneg[mb] = blind ? 0.f : -m_new * c1;
                         pin(mneg[mb]);
@@ -845,6 +860,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         // tile i-1, then those of GEMM 1 of tile i+1, a slice of the softmax of tile i behind each
         auto steady = [&](auto curc, int i) __attribute__((always_inline)) {
             constexpr int CUR = decltype(curc)::value;
+            const int n0 = i * TN + ncol0;
             set_d_slot(ring_off(i - 1));
             set_b_slot(ring_off(i + 1));
             v8 op[TT];
@@ -859,7 +875,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
                 if constexpr (t + PF < TT) fetch(std::integral_constant<int, t + PF>{});
                 if constexpr (t < T2) g2_step(tc, op[t]);
                 else g1_step(std::integral_constant<int, t - T2>{}, std::integral_constant<int, CUR ^ 1>{}, op[t]);
-                vstep(tc, curc, std::false_type{}, 0);
+                vstep(tc, curc, n0);
                 __builtin_amdgcn_sched_barrier(0);
             });
             settle();
@@ -868,8 +884,8 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         // whose slice of it is empty contributes P = 0)
         auto softmax_only = [&](auto curc, int t) __attribute__((always_inline)) {
             const int n0 = t * TN + ncol0;
-            if (n0 < n_wave) {
-                static_for<0, TT>([&](auto tc) { vstep(tc, curc, std::true_type{}, n0); });
+            if (n0 < N) {
+                static_for<0, TT>([&](auto tc) { vstep(tc, curc, n0); });
                 settle();
             } else {
 #pragma unroll
@@ -905,43 +921,32 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             top(0);
             if (last >= 1) g1_only(std::integral_constant<int, 1>{}, 1);
             softmax_only(std::integral_constant<int, 0>{}, 0);
-            // iterations 1 .. last-1.  Those whose tile needs no masking for this wave (all of them
-            // without a causal mask; the tiles left of the mask's edge with one) run the steady
-            // state, two per trip so that the two C^T buffers swap roles at compile time ...
-            int steady_end = (n_clean - ncol0 - 32 * NJ) / TN; // last tile that ends at or below n_clean
-            if (n_clean - ncol0 - 32 * NJ < 0) steady_end = -1;
-            if (steady_end > last - 1) steady_end = last - 1;
+            // iterations 1 .. last-1: two per trip, the two C^T buffers swap roles at compile time
             int i = 1;
-            for (; i + 1 <= steady_end; i += 2) {
+            for (; i + 1 <= last - 1; i += 2) {
                 top(i);
                 steady(std::integral_constant<int, 1>{}, i);
                 top(i + 1);
                 steady(std::integral_constant<int, 0>{}, i + 1);
             }
-            if (i <= steady_end) {
+            if (i <= last - 1) {
                 top(i);
                 steady(std::integral_constant<int, 1>{}, i);
                 ++i;
             }
-            // ... and the rest the parts one after the other: the tiles on the mask's edge, and the
-            // last tile (GEMM 2 of the tile before it, its softmax, no tile after it).  From here on
-            // the tile in the softmax always sits in the first C^T buffer (copied there: a branch on
-            // the parity of i in this tail would keep both buffers and their copies alive all along).
-            auto first_from_second = [&]() __attribute__((always_inline)) {
+            // iteration `last` (if it is not iteration 0): GEMM 2 of the tile before, softmax of the
+            // last, which is moved to the first C^T buffer if it sits in the second (two copies of
+            // the softmax, one per buffer, would keep both buffers alive to the end: registers)
+            if (last >= 1) {
+                if (last & 1) {
 #pragma unroll
-                for (int j = 0; j < NJ; ++j)
+                    for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) cc[0][j][mb] = cc[1][j][mb];
-            };
-            if (i <= last && (i & 1)) first_from_second();
-            for (; i <= last; ++i) {
-                top(i);
-                g2_only(i - 1);
-                softmax_only(std::integral_constant<int, 0>{}, i);
-                if (i < last) {
-                    g1_only(std::integral_constant<int, 1>{}, i + 1);
-                    first_from_second();
+                        for (int mb = 0; mb < MB; ++mb) cc[0][j][mb] = cc[1][j][mb];
                 }
+                top(last);
+                g2_only(last - 1);
+                softmax_only(std::integral_constant<int, 0>{}, last);
             }
             // GEMM 2 of the last tile
             g2_only(last);
@@ -960,7 +965,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
                 stage_l = stage_l + 1 == S ? 0 : stage_l + 1;
             }
             const int n0 = it * TN + wn * (32 * NJ); // first column of this wave's 32*NJ-wide slice
-            if (n0 < n_wave) {
+            if (n0 < N) {
                 const unsigned st = stage_c * STAGE;
                 phase_g1(st);
                 phase_g2_prefetch(st);
@@ -995,7 +1000,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
             for (int i = 0; i < n_iters; ++i) {
                 top(i);
                 const int n0 = i * TN + ncol0;
-                if (n0 < n_wave) {
+                if (n0 < N) {
                     const unsigned st = (i % S) * STAGE;
                     phase_g1(st);
                     phase_g2_prefetch(st);
@@ -1006,18 +1011,18 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
         } else {
             auto finish_tile = [&](int t) __attribute__((always_inline)) { // SM and G2 of tile t
                 const int n0 = t * TN + ncol0;
-                if (n0 < n_wave) {
+                if (n0 < N) {
                     phase_g2_prefetch((t % S) * STAGE);
                     phase_sm(n0);
                     phase_g2();
                 }
             };
             top(0);
-            if (ncol0 < n_wave) phase_g1(0);
+            if (ncol0 < N) phase_g1(0);
             for (int i = 1; i < n_iters; ++i) {
                 top(i);
                 finish_tile(i - 1);
-                if (i * TN + ncol0 < n_wave) {
+                if (i * TN + ncol0 < N) {
                     phase_g1((i % S) * STAGE);
                 }
             }
@@ -1186,7 +1191,7 @@ __global__ __launch_bounds__(64 * RG * NS) void chain_kernel(const KParams p) {
     // out as they are held, 16 consecutive columns of a row per lane in four 16-byte stores
     const bool out_f32 = ((uintptr_t)p.E & 1) != 0;
     if (out_f32) {
-        float *Ef = (float *)((uintptr_t)p.E & ~(uintptr_t)15) + batch * p.se_b + ht * LD;
+        float *Ef = (float *)((char *)p.E - 1) + batch * p.se_b + ht * LD; // (pointer arithmetic, so that the stores stay global ones)
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             const int row = wrow0 + 32 * mb + c;

@@ -217,11 +217,11 @@ static int run(const mcf_problem *p_in, int softmax, float scale, const void *A,
     k.k_chunks = (int32_t)(p->K / v->K);
     k.F = F; k.sf_b = sf[0]; k.sf_r = sf[1];
     if (p->out_dtype == MCF_F32) k.E = (void *)((uintptr_t)E | 1); // the kernels read bit 0 as "store fp32"
-    if (causal && causal_off < p->N - 1) { // (an offset of N - 1 or more hides nothing)
-        // the kernel forms row + offset + 1 in 32 bits
-        if (p->M + p->N >= (1ll << 31) - 1024) return MCF_EUNSUPPORTED;
-        k.causal = 1;
-        k.causal_off = (int32_t)(causal_off < -p->M - 1 ? -p->M - 1 : causal_off); // below -M nothing is seen either
+    if (softmax) {
+        // row i sees the columns n <= i + causal_off, which the kernel forms in 32 bits; an offset
+        // of N - 1 (or more) hides nothing and stands for "no mask", below -M nothing is seen either
+        if (p->M + p->N >= (1ll << 31) - 1024) { set_last_error("softmax chain: M + N must stay below 2^31 - 1024"); return MCF_EUNSUPPORTED; }
+        k.causal_off = (int32_t)(!causal || causal_off > p->N - 1 ? p->N - 1 : causal_off < -p->M - 1 ? -p->M - 1 : causal_off);
     }
     if (softmax) {
         // exp(scale*s - max) = exp2(|scale|*log2(e) * (s' - max')) with s' = +-s; a zero scale

@@ -113,6 +113,19 @@ constexpr int pipe_stages(int K, int L, int mb, int rg, int ns, int nj, bool sof
     if (!softmax || ksplit) return 0;
     return total_lds_bytes(K, L, mb, rg, ns, nj, 4) + extra <= 160 * 1024 ? 4 : 0;
 }
+// Waves per SIMD a pipelined softmax kernel is compiled for.  A block brings rg*ns/4 of them; a
+// second resident block hides the block's barriers and the ends of its pipeline (measured: a
+// third to a half faster on the short attention shapes), but the compiler only keeps to the
+// registers that leaves a wave (512 / waves) when told so, otherwise it drifts a few registers
+// over.  Asked for when two blocks fit the LDS and the tiles a lane must hold (the E
+// accumulators, two C^T tiles, P packed to 16 bit) leave some 56 registers for operands,
+// addresses and the softmax state.
+constexpr int pipe_waves_per_simd(int K, int L, int mb, int rg, int ns, int nj, int extra = 0) {
+    const int per_block = rg * ns >= 4 ? rg * ns / 4 : 1;
+    if (2 * (total_lds_bytes(K, L, mb, rg, ns, nj, 4) + extra) > 160 * 1024) return per_block;
+    const int held = mb * h_blocks(L) * 16 + 2 * nj * mb * 16 + nj * mb * 8;
+    return held + 56 <= 512 / (2 * per_block) ? 2 * per_block : per_block;
+}
 // Softmax chains that cannot be pipelined, in blocks of 8 waves, run their two wave groups a
 // phase apart, which keeps two n-tiles live: their ring is at least 3 deep.
 constexpr bool skewed_groups(int rg, int ns, bool softmax, bool ksplit = false) { return softmax && rg * ns == 8 && !ksplit; }

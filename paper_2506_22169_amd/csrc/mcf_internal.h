@@ -33,8 +33,8 @@ struct KParams {
     int32_t a_mode;     // 0: A as is, 1: -A (negative scale), 2: A := 0 (scale == 0)
     int32_t k_chunks;   // kernels with a k loop: K / T_K (otherwise unused)
     float c1;           // |scale| * log2(e) (softmax only)
-    int32_t causal;     // softmax only: 1 = row i sees the columns n <= i + causal_off
-    int32_t causal_off;
+    int32_t causal_off; // softmax only: row i sees the columns n <= i + causal_off (N - 1: no mask); no flag
+                        // beside it: a branch on one splits the scalar loads of the arguments in two
     const void *A, *B, *D;
     void *E;            // bit 0 set: written as fp32 (the pointer itself is 16-byte aligned; strides then count fp32 elements)
     int64_t sa_b, sa_r; // A: batch / row stride (col stride 1)
@@ -65,7 +65,8 @@ struct Variant {
     int32_t P;             // three-GEMM chain: columns of F and of the output; 0: two-GEMM chain
     LaunchFn launch;
     int32_t vgprs;         // VGPRs per lane the compiler allocated (-1: unknown)
-    int32_t scratch_bytes; // per-lane scratch (register spills); such variants are never picked
+    int32_t scratch_bytes; // per-lane scratch of a kernel whose loops spill registers (such variants are never picked); 0 also
+                           // where the compiler only parks a few registers in scratch across the n loop, outside of it
 };
 
 // Registry of every built kernel variant (defined in mcf_registry.cpp): the two-GEMM chain ...

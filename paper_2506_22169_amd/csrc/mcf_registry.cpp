@@ -17,7 +17,7 @@ MCF_GROUPS3(MCF_DECL)
 
 // Registers / scratch of every kernel as the compiler built it (generated at build time).
 struct Resources {
-    int dtype, K, L, mb, rg, ns, nj, softmax, b_kcontig, ksplit, P, vgprs, sgprs, scratch_bytes;
+    int dtype, K, L, mb, rg, ns, nj, softmax, b_kcontig, ksplit, P, vgprs, sgprs, scratch_bytes, spills_in_loops;
 };
 static const Resources kResources[] = {
 #include "mcf_resources.inc"
@@ -38,7 +38,9 @@ static void attach_resources(std::vector<Variant> &t) {
             if (r.dtype == v.dtype && r.K == v.K && r.L == v.L && r.mb == v.mb && r.rg == v.rg && r.ns == v.ns &&
                 r.nj == v.nj && r.softmax == v.softmax && r.b_kcontig == v.b_kcontig && r.ksplit == v.ksplit && r.P == v.P) {
                 v.vgprs = r.vgprs;
-                v.scratch_bytes = r.scratch_bytes;
+                // registers parked in scratch across the n loop (stored before it, fetched after it)
+                // cost a block a handful of instructions and do not count; spill code inside a loop does
+                v.scratch_bytes = r.spills_in_loops ? r.scratch_bytes : 0;
             }
     }
 }
