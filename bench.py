@@ -9,13 +9,15 @@ input/output sets (> 768 MiB in total) that every step's operands come from HBM.
 
 Protocol (the same for every workload and for the ceilings):
   1. --warmup untimed steps (they also set kernel attributes before any capture);
-  2. the --steps steps are captured once into a HIP graph (each step is still one call of the
-     C ABI on the capturing stream; the host-side tile pick runs at capture);
+  2. the --steps steps, rounded up to whole rotations over the buffer sets (a graph of 20 steps
+     would replay the same 20 sets for ever, a third of which the memory-side cache can hold),
+     are captured once into a HIP graph (each step is still one call of the C ABI on the
+     capturing stream; the host-side tile pick runs at capture);
   3. an untimed clock ramp: the graph is replayed until at least RAMP_MS of device time have
      passed, whatever --warmup says (a cold engine clock makes a launch up to a third slower);
   4. the timed region is `replays` back-to-back replays of that graph, as many as it takes to
      fill MIN_REGION_MS, bracketed by synchronize on both sides.  `ms_per_step` and `value`
-     come from the host clock around the region divided by steps x replays;
+     come from the host clock around the region divided by the steps of the graph x replays;
      `us_per_launch_events` from HIP events on the launch stream around the same region.
 --eager times plain calls instead of graph replays (the tile pick is then inside every step).
 
@@ -78,7 +80,10 @@ def parse_args():
 class Timer:
     """The protocol of the module docstring around any `step(i)`."""
 
-    def __init__(self, torch, steps, warmup, eager=False):
+    def __init__(self, torch, steps, warmup, eager=False, rotate=1):
+        # the graph holds whole rotations over the buffer sets: a short graph would only ever touch the
+        # first few sets, which together may fit the 256 MB memory-side cache in front of HBM
+        steps = (steps + rotate - 1) // rotate * rotate
         self.torch, self.steps, self.warmup, self.eager = torch, steps, warmup, eager
 
     def measure(self, step):
@@ -126,8 +131,8 @@ class Timer:
         wall_s = time.perf_counter() - t0
         dev_s = e0.elapsed_time(e1) * 1e-3
         n = self.steps * replays
-        return {"t_step": wall_s / n, "t_kernel": dev_s / n, "replays": replays, "clock_ramp_launches": ramp_launches,
-                "clock_ramp_ms": ramp_ms}
+        return {"t_step": wall_s / n, "t_kernel": dev_s / n, "replays": replays, "graph_steps": self.steps,
+                "clock_ramp_launches": ramp_launches, "clock_ramp_ms": ramp_ms}
 
 
 def run_ceilings(args, torch, mcf):
@@ -281,7 +286,7 @@ def main():
     pick_us = (time.perf_counter() - tp0) / 200 * 1e6
     picked = picked_auto if tiles is None else mcf.eval_tiles(prob, *tiles, softmax=w.softmax)
 
-    m = Timer(torch, args.steps, args.warmup, args.eager).measure(step)
+    m = Timer(torch, args.steps, args.warmup, args.eager, rotate=n_sets).measure(step)
     t_step, t_kernel = m["t_step"], m["t_kernel"]
 
     if args.copy_ref:
@@ -358,7 +363,7 @@ def main():
                    "tiles": {"mb": picked.mb, "rg": picked.rg, "ns": picked.ns, "nj": picked.nj, "tm": picked.tm,
                              "tn": picked.tn, "tk": picked.tk, "tl": picked.tl, "stages": picked.stages},
                    "buffer_sets": n_sets, "launch": "eager" if args.eager else "hip_graph",
-                   "replays": m["replays"], "timed_steps": args.steps * m["replays"],
+                   "replays": m["replays"], "graph_steps": m["graph_steps"], "timed_steps": m["graph_steps"] * m["replays"],
                    "clock_ramp_launches": m["clock_ramp_launches"], "clock_ramp_ms": round(m["clock_ramp_ms"], 1),
                    "tile_choice": "search" if search else ("given" if args.tiles else "model"), "search": search},
         "pct_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS, "tflops": tflops,
