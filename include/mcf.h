@@ -241,6 +241,65 @@ int mcf_tune_tiles(const mcf_problem *problem, int softmax, float scale, const v
                    mcf_search_report *report_or_null);
 
 /*
+ * Search-space generation and pruning (Sec. III-A, III-B, III-C).  Host only.  The paper's space
+ * is (tiling expressions) x (tile sizes); the kernels of this library are points of what is left
+ * of it after Rules 1-4, and these entry points say which.
+ *
+ * A tiling expression is written as in the paper: `xy` nests loop y in loop x, `(x,y)` runs x and
+ * then y in one scope; the loops are m, n, k, h (h is this library's L).  Extents arrays are in
+ * the order m, n, k, h.
+ *
+ * mcf_expression      : the index-th (0..25) of the 24 deep expressions (the permutations of
+ *                       m n k h) followed by the two flat ones, mn(k,h) and nm(k,h); out is a
+ *                       caller buffer of cap >= 8 bytes.  MCF_EINVAL beyond the last.
+ * mcf_expression_trips: how often each statement of `expr` runs, trips[] in the order C_C, C_E,
+ *                       L_A, L_B, L_D, S_E (Sec. III-B): a compute statement sits under the
+ *                       rightmost loop related to it, a memory statement under the rightmost loop
+ *                       that indexes its tensor, loops of extent 1 hold nothing.  flags:
+ *                       MCF_TRIPS_NO_HOIST leaves the memory statements beside their compute
+ *                       statement, MCF_TRIPS_KEEP_UNIT_LOOPS keeps loops of extent 1 in place,
+ *                       MCF_TRIPS_BIND_BLOCK keeps every statement inside the loops Rule 1 binds
+ *                       to the block index (blocks share no on-chip memory).  MCF_EINVAL for a
+ *                       string that is no expression over exactly m, n, k, h.
+ * mcf_sub_expression  : Rule 1: what a block runs once m and h are bound to the block index (in
+ *                       a flat expression h shares a scope with k and stays), into the caller
+ *                       buffer out of cap >= 8 bytes; *passes_rule2 (may be NULL) = 0 if in it k
+ *                       encloses n (one partial tile of the intermediate tensor per n), else 1.
+ *                       MCF_EINVAL as above.
+ * mcf_enumerate_space : the sizes Sec. III-C follows through its example, for this problem:
+ *                       expressions, sub-expressions after Rule 1 and after Rule 2, tile-size
+ *                       combinations (multiples of 16 up to each dimension) before and after
+ *                       Rule 3 (padding) and Rule 4 (eq. (1) over all five tiles in bytes against
+ *                       1.2 x shm_max_bytes; 0 = the 160 KiB of a compute unit), and how many of
+ *                       the surviving points a built kernel runs.  This reading of Rules 1 and 2
+ *                       leaves 3 and then 2 sub-expressions (nk, kn, n(k,h); kn falls); the paper
+ *                       counts 5 and 3 without listing them.  MCF_EUNSUPPORTED for a dimension
+ *                       beyond 2^24.
+ */
+#define MCF_MAX_SUB_EXPRESSIONS 8
+enum { MCF_TRIPS_NO_HOIST = 1, MCF_TRIPS_KEEP_UNIT_LOOPS = 2, MCF_TRIPS_BIND_BLOCK = 4 };
+typedef struct mcf_space_report {
+    int32_t n_deep, n_flat;       /* 24, 2                                                       */
+    int32_t n_rule1, n_rule2;     /* distinct sub-expressions; those that pass Rule 2            */
+    char sub_expression[MCF_MAX_SUB_EXPRESSIONS][16];
+    int32_t sub_members[MCF_MAX_SUB_EXPRESSIONS]; /* expressions that reduce to each             */
+    int32_t sub_kept[MCF_MAX_SUB_EXPRESSIONS];    /* 1: passes Rule 2                            */
+    int64_t tile_choices;         /* prod ceil(dim / 16) over M, N, K, L                         */
+    int64_t after_rule3;          /* combinations whose four tile sizes pass the padding rule    */
+    int64_t after_rule4;          /* of those, the ones eq. (1) lets on chip                     */
+    int64_t candidates;           /* (n_deep + n_flat) * tile_choices                            */
+    int64_t candidates_pruned;    /* n_rule2 * after_rule4                                       */
+    int64_t built_deep;           /* surviving points (nk, T_M, T_N, T_K, T_H) a kernel runs: T_L = T_H, */
+                                  /* the h tiles blocks of their own                             */
+    int64_t built_flat;           /* surviving points (n(k,h), T_M, T_N, T_K, 32) a kernel runs:  */
+                                  /* T_L = L, E tiles of every 32-column h step in registers     */
+} mcf_space_report;
+int mcf_expression(int index, char *out, int cap);
+int mcf_expression_trips(const char *expr, const int64_t extents[4], int flags, int64_t trips[6]);
+int mcf_sub_expression(const char *expr, char *out, int cap, int *passes_rule2);
+int mcf_enumerate_space(const mcf_problem *problem, int softmax, int64_t shm_max_bytes, mcf_space_report *out);
+
+/*
  * Measurement aids (no part of the chain): the kernels whose times bound what the chain kernel
  * can reach -- Sec. IV-A's W and P as this machine delivers them, and the cost of a launch.
  * All asynchronous on hip_stream, device pointers owned by the caller, nothing allocated.

@@ -44,6 +44,24 @@ class Tiles(ctypes.Structure):
         return {n: getattr(self, n) for n, _ in self._fields_}
 
 
+MCF_MAX_SUB_EXPRESSIONS = 8
+MCF_TRIPS_NO_HOIST, MCF_TRIPS_KEEP_UNIT_LOOPS, MCF_TRIPS_BIND_BLOCK = 1, 2, 4
+
+
+class SpaceReport(ctypes.Structure):
+    """struct mcf_space_report"""
+    _fields_ = [("n_deep", ctypes.c_int32), ("n_flat", ctypes.c_int32), ("n_rule1", ctypes.c_int32), ("n_rule2", ctypes.c_int32),
+                ("sub_expression", (ctypes.c_char * 16) * MCF_MAX_SUB_EXPRESSIONS),
+                ("sub_members", ctypes.c_int32 * MCF_MAX_SUB_EXPRESSIONS), ("sub_kept", ctypes.c_int32 * MCF_MAX_SUB_EXPRESSIONS),
+                ("tile_choices", ctypes.c_int64), ("after_rule3", ctypes.c_int64), ("after_rule4", ctypes.c_int64),
+                ("candidates", ctypes.c_int64), ("candidates_pruned", ctypes.c_int64),
+                ("built_deep", ctypes.c_int64), ("built_flat", ctypes.c_int64)]
+
+    def subs(self):
+        """{sub-expression: (members, kept)}"""
+        return {self.sub_expression[i].value.decode(): (self.sub_members[i], bool(self.sub_kept[i])) for i in range(self.n_rule1)}
+
+
 class SearchParams(ctypes.Structure):
     """struct mcf_search_params"""
     _fields_ = [("population", ctypes.c_int32), ("top_n", ctypes.c_int32), ("max_generations", ctypes.c_int32),
@@ -109,6 +127,12 @@ def load_library():
     lib.mcf_probe_mfma.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp]
     lib.mcf_probe_empty.argtypes = [ctypes.c_int32, vp]
     for f in (lib.mcf_probe_copy, lib.mcf_probe_mfma, lib.mcf_probe_empty):
+        f.restype = ctypes.c_int
+    lib.mcf_expression.argtypes = [ctypes.c_int, ctypes.c_char_p, ctypes.c_int]
+    lib.mcf_expression_trips.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_int64), ctypes.c_int, ctypes.POINTER(ctypes.c_int64)]
+    lib.mcf_sub_expression.argtypes = [ctypes.c_char_p, ctypes.c_char_p, ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
+    lib.mcf_enumerate_space.argtypes = [PP, ctypes.c_int, ctypes.c_int64, ctypes.POINTER(SpaceReport)]
+    for f in (lib.mcf_expression, lib.mcf_expression_trips, lib.mcf_sub_expression, lib.mcf_enumerate_space):
         f.restype = ctypes.c_int
     lib.mcf_status_string.argtypes = [ctypes.c_int]
     lib.mcf_status_string.restype = ctypes.c_char_p
@@ -386,6 +410,38 @@ def list_variants3(problem, P, softmax=False):
     buf = (ctypes.c_int32 * (4 * max(n, 1)))()
     lib.mcf_list_variants3(ctypes.byref(problem), int(P), int(bool(softmax)), buf, n)
     return [tuple(buf[4 * i:4 * i + 4]) for i in range(n)]
+
+
+def expressions():
+    """mcf_expression: the 24 deep and the 2 flat tiling expressions of Sec. III-A; host only."""
+    lib, out, buf = load_library(), [], ctypes.create_string_buffer(16)
+    i = 0
+    while lib.mcf_expression(i, buf, 16) == MCF_OK:
+        out.append(buf.value.decode())
+        i += 1
+    return out
+
+
+def expression_trips(expr, extents, flags=0):
+    """mcf_expression_trips: {statement: trips} for extents given as a dict over 'mnkh'; host only."""
+    ext = (ctypes.c_int64 * 4)(*(int(extents[l]) for l in "mnkh"))
+    t = (ctypes.c_int64 * 6)()
+    _check(load_library().mcf_expression_trips(expr.encode(), ext, int(flags), t))
+    return dict(zip(("C_C", "C_E", "L_A", "L_B", "L_D", "S_E"), t))
+
+
+def sub_expression(expr):
+    """mcf_sub_expression: (what a block runs under Rule 1, whether that passes Rule 2); host only."""
+    buf, ok = ctypes.create_string_buffer(16), ctypes.c_int(0)
+    _check(load_library().mcf_sub_expression(expr.encode(), buf, 16, ctypes.byref(ok)))
+    return buf.value.decode(), bool(ok.value)
+
+
+def enumerate_space(problem, softmax=False, shm_max_bytes=0):
+    """mcf_enumerate_space: the sizes of the search space before and after Rules 1-4; host only."""
+    r = SpaceReport()
+    _check(load_library().mcf_enumerate_space(ctypes.byref(problem), int(bool(softmax)), int(shm_max_bytes), ctypes.byref(r)))
+    return r
 
 
 def probe_copy(dst, src, stream=None):
