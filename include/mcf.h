@@ -130,7 +130,8 @@ int mcf_gemm_chain(const mcf_problem *problem, const void *A, const void *B, con
 /*
  * E = softmax_rows(scale * A . B) . D   (Sec. VI-B2; softmax along n, no mask).  The kernel
  * uses the online max / sum recurrence over n-tiles, which equals the two-pass definition up
- * to rounding.  Same argument rules as mcf_gemm_chain; N == 0 is MCF_EINVAL.
+ * to rounding.  Same argument rules as mcf_gemm_chain; N == 0 is MCF_EINVAL, M + N at or beyond
+ * 2^31 - 1024 MCF_EUNSUPPORTED (the kernels compare row and column numbers in 32 bits).
  */
 int mcf_softmax_gemm_chain(const mcf_problem *problem, float scale, const void *A,
                            const void *B, const void *D, void *E,
@@ -141,8 +142,9 @@ int mcf_softmax_gemm_chain(const mcf_problem *problem, float scale, const void *
  * kernels): row i of every batch sees the columns n <= i + causal_offset only,
  *     E[b,i,:] = softmax_{n <= i + causal_offset}(scale * A[b,i,:] . B[b,:,n]) . D[b,n,:],
  * causal_offset = 0 being the lower triangle and causal_offset = N - M the triangle that ends
- * in the last row and column; a row that sees no column is written as zeros.  n-tiles that no
- * row of a block sees are neither loaded nor computed.  Everything else as
+ * in the last row and column (any offset is valid: N - 1 or more hides nothing, -M or less
+ * everything); a row that sees no column is written as zeros.  n-tiles that no row of a block
+ * sees are neither loaded nor computed.  Everything else as
  * mcf_softmax_gemm_chain (same kernels, same tile choice).
  */
 int mcf_causal_softmax_gemm_chain(const mcf_problem *problem, float scale, int64_t causal_offset,
