@@ -158,8 +158,10 @@ int mcf_causal_softmax_gemm_chain(const mcf_problem *problem, float scale, int64
  * (NULL or all zero = packed; col stride 1), G is [batch, M, P] and problem->e_stride
  * describes G (not E, which never leaves the registers).  E is rounded once to in_dtype
  * before the third GEMM, as C / P is before the second (with a split of n across waves: each
- * wave's normalised partial E).  Built for (K, L, P) in {(64,64,64), (128,128,128)}; other
- * shapes give MCF_EUNSUPPORTED.  tiles_or_null: NULL = the arrangement whose two-GEMM part
+ * wave's normalised partial E).  Built for (K, L, P) in {(64,64,64), (128,128,128),
+ * (64,128,128), (128,64,64), (64,64,128)} (with P != L only arrangements without a split of n
+ * across waves: the combine of the product reuses the register layout of E); other shapes
+ * give MCF_EUNSUPPORTED.  tiles_or_null: NULL = the arrangement whose two-GEMM part
  * the model ranks best among those built for three GEMMs, otherwise its mb, rg, ns, nj are
  * read.  G must not overlap A, B, D or F.
  */

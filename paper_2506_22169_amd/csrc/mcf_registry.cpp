@@ -10,7 +10,9 @@ namespace mcf {
     X(bf16_32_32) X(bf16_64_64) X(bf16_128_128) X(bf16_64_128) X(bf16_128_64) X(bf16_64_256) X(bf16_256_256)      \
     X(f16_k128x_64) X(f16_k128x_128) X(f16_k128x_256) X(bf16_k128x_64) X(bf16_k128x_128) X(bf16_k128x_256)      \
     X(f16_80_80) X(bf16_80_80) X(f16_96_96) X(bf16_96_96) X(f16_160_160) X(bf16_160_160) X(f16_192_192) X(bf16_192_192)
-#define MCF_GROUPS3(X) X(f16_c3_64_64_64) X(f16_c3_128_128_128) X(bf16_c3_64_64_64) X(bf16_c3_128_128_128)
+#define MCF_GROUPS3(X)                                                                                     \
+    X(f16_c3_64_64_64) X(f16_c3_128_128_128) X(bf16_c3_64_64_64) X(bf16_c3_128_128_128)                    \
+    X(f16_c3_64_128_128) X(f16_c3_128_64_64) X(f16_c3_64_64_128) X(bf16_c3_64_128_128) X(bf16_c3_128_64_64) X(bf16_c3_64_64_128)
 #define MCF_DECL(NAME) const Variant *variants_##NAME(int *count);
 MCF_GROUPS(MCF_DECL)
 MCF_GROUPS3(MCF_DECL)

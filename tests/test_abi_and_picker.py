@@ -196,25 +196,26 @@ def test_rule3_fallback_and_ragged_shapes():
 
 
 def test_three_gemm_chain_host_side():
-    """Arrangements built for the three-GEMM chain, for (K, L, P) in {(64,64,64), (128,128,128)}:
-    a subset of those of the two-GEMM chain, with and without a split of n across waves; the
-    default pick is one of them, one with the smallest two-GEMM estimate; other shapes are
-    refused."""
-    for K in (64, 128):
+    """Arrangements built for the three-GEMM chain, for (K, L, P) in {(64,64,64), (128,128,128), (64,128,128),
+    (128,64,64), (64,64,128)}: a subset of those of the two-GEMM chain, with and without a split of n across
+    waves where P = L (the combine of the product reuses the layout of E), without one where P != L; the
+    default pick is one of them, one with the smallest two-GEMM estimate; other shapes are refused."""
+    for K, L, P in ((64, 64, 64), (128, 128, 128), (64, 128, 128), (128, 64, 64), (64, 64, 128)):
         for dtype in ("f16", "bf16"):
             for softmax in (False, True):
-                prob = make_problem(8, 1024, K, 1024, K, dtype, b_stride=(1024 * K, 1, K) if softmax else None)
-                shapes = mcf.list_variants3(prob, K, softmax)
-                assert len(shapes) >= 8 and {s[2] for s in shapes} >= {1, 2}
+                prob = make_problem(8, 1024, K, 1024, L, dtype, b_stride=(1024 * K, 1, K) if softmax else None)
+                shapes = mcf.list_variants3(prob, P, softmax)
+                assert len(shapes) >= 4
+                assert {s[2] for s in shapes} >= ({1, 2} if P == L else {1}) and (P == L or {s[2] for s in shapes} == {1})
                 assert set(shapes) <= set(mcf.list_variants(prob, softmax))
-                t = mcf.pick_tiles3(prob, K, softmax)
+                t = mcf.pick_tiles3(prob, P, softmax)
                 assert (t.mb, t.rg, t.ns, t.nj) in shapes
                 ests = {s: mcf.eval_tiles(prob, *s, softmax=softmax).t_est_s for s in shapes}
                 assert t.t_est_s == min(ests.values())
     prob = make_problem(8, 1024, 64, 1024, 64, "f16")
     assert mcf.list_variants3(prob, 32, False) == []
     with pytest.raises(mcf.McfError) as e:
-        mcf.pick_tiles3(prob, 128, False)
+        mcf.pick_tiles3(prob, 256, False)
     assert e.value.status == 2
     with pytest.raises(mcf.McfError) as e:
         mcf.pick_tiles3(make_problem(8, 1024, 32, 1024, 32, "f16"), 32, False)

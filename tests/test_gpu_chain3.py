@@ -31,21 +31,21 @@ def _check(G, ref, what):
 
 @pytest.mark.parametrize("softmax", [False, True])
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-@pytest.mark.parametrize("KLP", [(64, 64, 64), (128, 128, 128)])
+@pytest.mark.parametrize("KLP", [(64, 64, 64), (128, 128, 128), (64, 128, 128), (128, 64, 64), (64, 64, 128)])
 def test_chain3_every_variant_small_ragged(KLP, dtype, softmax):
     """Every arrangement built for three GEMMs, on ragged m and n tails over several tiles."""
     K, L, P = KLP
     M, N = 600, (584 if not softmax else 589)
-    w, x, f_bits, F64 = _inputs(3, M, K, N, L, P, dtype, softmax, seed=9000 + K)
+    w, x, f_bits, F64 = _inputs(3, M, K, N, L, P, dtype, softmax, seed=9000 + K + 3 * L + 7 * P)
     ref = oracle.chain3(x["A"], x["B"], x["D"], F64, softmax=softmax, scale=w.scale)
     A, B, D = device_inputs(w, x)
     F = to_device(f_bits, dtype)
     prob = c_problem(3, M, K, N, L, dtype, b_stride=(N * K, 1, K) if softmax else None)
     shapes = mcf.list_variants3(prob, P, softmax)
-    assert len(shapes) >= 6
+    assert len(shapes) >= 4
     worst = 0.0
     for tiles in shapes + [None]:
-        print(f"case chain3 K={K} {dtype} softmax={softmax} tiles={tiles}", flush=True)
+        print(f"case chain3 K={K} L={L} P={P} {dtype} softmax={softmax} tiles={tiles}", flush=True)
         G = mcf.gemm_chain3(A, B, D, F, scale=w.scale if softmax else None, tiles=tiles)
         torch.cuda.synchronize()
         worst = max(worst, _check(to_host64(G, dtype), ref, f"K={K} {dtype} softmax={softmax} tiles={tiles}"))
@@ -106,7 +106,7 @@ def test_chain3_random_sweep():
     sizes = [1, 2, 7, 31, 32, 33, 64, 100, 129, 255, 300, 517]
     worst = 0.0
     for case in range(n_cases):
-        K = L = P = (64, 128)[rng.integers(2)]
+        K, L, P = ((64, 64, 64), (128, 128, 128), (64, 128, 128), (128, 64, 64), (64, 64, 128))[rng.integers(5)]
         dtype = ("f16", "bf16")[rng.integers(2)]
         softmax = bool(rng.integers(2))
         nk = bool(rng.integers(2))
