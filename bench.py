@@ -142,7 +142,7 @@ def run_ceilings(args, torch, mcf):
 
     def copy_case(total_bytes, rotate_bytes):
         half = total_bytes // 2                                 # read half, write half
-        n_sets = max(2, min(64, rotate_bytes // total_bytes))
+        n_sets = max(2, min(64 if total_bytes >= 2**20 else 1024, rotate_bytes // total_bytes))
         srcs = [torch.full((half // 2,), 1.0, dtype=torch.float16, device="cuda") for _ in range(n_sets)]
         dsts = [torch.empty_like(s) for s in srcs]
         r = timer.measure(lambda i: mcf.probe_copy(dsts[i % n_sets], srcs[i % n_sets]))
@@ -151,6 +151,8 @@ def run_ceilings(args, torch, mcf):
                 "gbs": total_bytes / r["t_kernel"] / 1e9, "frac_of_hbm_peak": total_bytes / r["t_kernel"] / 1e9 / HBM_PEAK_GBS,
                 "replays": r["replays"]}
 
+    out["copy_288KiB"] = copy_case(288 * 2**10, 1024 * 2**20)   # cfg1's compulsory bytes: what a load -> store chain costs a launch
+    out["copy_10MiB"] = copy_case(10 * 2**20, 1024 * 2**20)     # cfg4's
     out["copy_16MiB"] = copy_case(16 * 2**20, 1024 * 2**20)     # cfg2's compulsory bytes, operands from HBM
     out["copy_24MiB"] = copy_case(24 * 2**20, 1024 * 2**20)     # cfg3's
     out["copy_1GiB"] = copy_case(2**30, 4 * 2**30)
