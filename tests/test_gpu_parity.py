@@ -192,10 +192,11 @@ def test_error_codes_from_the_abi():
 
 
 def test_random_shapes_strides_and_tiles():
-    """Seeded sweep: random (K, L) group, dtype, chain kind, B layout, ragged or tiny M and N,
-    non-packed row and batch strides on every operand and on the output, and a random built
-    wave arrangement, each compared with the oracle element by element; the padding around a
-    strided output must come back untouched."""
+    """Seeded sweep: random (K, L) group, dtype, chain kind (plain, softmax, softmax under a causal
+    mask with a random offset), output type (the input type or fp32), B layout, ragged or tiny M
+    and N, non-packed row and batch strides on every operand and on the output, and a random
+    built wave arrangement, each compared with the oracle element by element; the padding around
+    a strided output must come back untouched."""
     # MCF_SWEEP_SEED / MCF_SWEEP_CASES: a longer or different sweep for a one-off run
     rng = np.random.default_rng(int(os.environ.get("MCF_SWEEP_SEED", "20250622")))
     n_cases = int(os.environ.get("MCF_SWEEP_CASES", "72"))
@@ -214,6 +215,9 @@ def test_random_shapes_strides_and_tiles():
         if not nk:
             N = max(8, (N + 7) // 8 * 8)                            # N-contiguous B: N a multiple of 8
         pad = [int(8 * rng.integers(0, 3)) for _ in range(4)]       # extra row pitch of A, B, D, E
+        causal = softmax and bool(rng.integers(2))
+        offset = int((0, N - M, -M - 2, N, int(rng.integers(-M, N + 1)), int(rng.integers(-8, 9)))[rng.integers(6)]) if causal else None
+        f32 = not rng.integers(3)                                   # fp32 output: every third case
         gap = [int(rng.integers(0, 3)) for _ in range(4)]           # extra rows between batches
         w = mi.make_problem(b, M, K, N, L, dtype, softmax, "normal" if softmax else "uniform", seed=9000 + case)
         x = mi.make_inputs(w)
@@ -235,20 +239,25 @@ def test_random_shapes_strides_and_tiles():
         else:
             _, B = strided(Bkn, K, N, pad[1], gap[1])
         _, D = strided(D0, N, L, pad[2], gap[2])
-        Ebig, E = strided(torch.zeros((b, M, L), dtype=tdt, device="cuda"), M, L, pad[3], gap[3], fill=5.0)
+        Ebig = torch.full((b, M + gap[3], L + pad[3]), 5.0, dtype=torch.float32 if f32 else tdt, device="cuda")
+        E = Ebig[:, :M, :L]
         prob = mcf.binding._problem_from_tensors(A, B, D, E)
         shapes = [(t.mb, t.rg, t.ns, t.nj, t.tl) for t in mcf.list_candidates(prob, softmax)]   # all T_L options
         shapes += [s for s in mcf.list_variants(prob, softmax)]           # and arrangements Rule 3 / the LDS rule would drop
         tiles = shapes[rng.integers(len(shapes))] if case % 4 else None   # every fourth case: the picker
-        print(f"case {case}: b={b} M={M} K={K} N={N} L={L} {dtype} softmax={softmax} nk={nk} pad={pad} gap={gap} "
-              f"tiles={tiles}", flush=True)
-        if softmax:
+        print(f"case {case}: b={b} M={M} K={K} N={N} L={L} {dtype} softmax={softmax} causal={offset} f32={f32} nk={nk} "
+              f"pad={pad} gap={gap} tiles={tiles}", flush=True)
+        if causal:
+            mcf.causal_softmax_gemm_chain(A, B, D, w.scale, causal_offset=offset, out=E, tiles=tiles)
+            ref = oracle.chain_causal(x["A"], x["B"], x["D"], w.scale, offset)
+        elif softmax:
             mcf.softmax_gemm_chain(A, B, D, w.scale, out=E, tiles=tiles)
         else:
             mcf.gemm_chain(A, B, D, out=E, tiles=tiles)
         torch.cuda.synchronize()
-        ref = oracle.chain(x["A"], x["B"], x["D"], softmax=softmax, scale=w.scale)
-        got = to_host64(E, dtype)
+        if not causal:
+            ref = oracle.chain(x["A"], x["B"], x["D"], softmax=softmax, scale=w.scale)
+        got = E.double().cpu().numpy() if f32 else to_host64(E, dtype)
         scale = np.max(np.abs(ref))
         err = np.max(np.abs(got - ref))
         assert err <= TOL * scale, f"case {case}: {err} > {TOL} * {scale}"
