@@ -17,6 +17,9 @@ Readings taken where the text is ambiguous or at odds with itself:
     "a factor of k", but in that expression S_E sits in the scope of n, not k; by the volume
     rule stated two sentences earlier the saving is the extent of n.  volume() follows the rule.
   * "tile size" in eq. (1) and (3) is taken in bytes (elements * element size).
+  * eq. (5): alpha = (N_block + N_SM) / N_block is the printed form; alpha_rounds() is the same
+    quantity for blocks that run in whole rounds (the printed form is its smooth upper bound).
+    estimate() computes either.
   * The dead-loop rule of Sec. III-B would hoist a load out of every loop once all loops that
     index its tensor have extent 1 (e.g. L_B when T_N = N and T_K = K).  Blocks share no
     on-chip memory, so in estimate() no statement leaves the loops bound to the block index
@@ -114,7 +117,15 @@ def extents_of(dims, tiles):
     return {l: ceil(dims[l] / tiles[l]) for l in LOOPS}
 
 
-def estimate(order, dims, tiles, batch, elem_bytes, W, P, n_units, W_reread=None):
+def alpha_rounds(n_block, n_units):
+    """eq. (5) read for a machine that runs blocks in rounds: n_units blocks run at a time, a
+    launch takes ceil(n_block / n_units) rounds, and alpha is the capacity of those rounds over
+    the blocks that fill it.  It never exceeds the printed (N_block + N_SM) / N_block, which is
+    its smooth upper envelope (ceil(x) <= x + 1), and is 1 for a launch that fills whole rounds."""
+    return ceil(n_block / n_units) * n_units / n_block
+
+
+def estimate(order, dims, tiles, batch, elem_bytes, W, P, n_units, W_reread=None, rounds=False):
     """eq. (2)-(5) for a deep tiling of the two-GEMM chain.
 
     dims/tiles: dicts over 'mnkh'.  Spatial loops m, h and the batch are bound to the block
@@ -123,6 +134,7 @@ def estimate(order, dims, tiles, batch, elem_bytes, W, P, n_units, W_reread=None
     W_reread: if given, bytes beyond the first touch of each tensor are charged at this
     bandwidth (the on-die cache that serves re-reads) and the compulsory bytes at W; with
     W_reread None every byte is charged at W exactly as eq. (3) is printed.
+    rounds: alpha as alpha_rounds() instead of the printed (N_block + N_SM) / N_block.
     """
     ext = extents_of(dims, tiles)
     blk = "mh"   # with the batch, the loops on the block index: nothing is hoisted out of a block
@@ -140,7 +152,7 @@ def estimate(order, dims, tiles, batch, elem_bytes, W, P, n_units, W_reread=None
         t_mem = compulsory / W + max(total - compulsory, 0) / W_reread
     t_comp = sum(flops.values()) / P
     n_block = batch * ext["m"] * ext["h"]
-    alpha = (n_block + n_units) / n_block
+    alpha = alpha_rounds(n_block, n_units) if rounds else (n_block + n_units) / n_block
     return {"mem_bytes": mem, "model_bytes": total, "compulsory_bytes": compulsory,
             "flops": sum(flops.values()), "t_mem": t_mem, "t_comp": t_comp,
             "n_block": n_block, "alpha": alpha, "t_estm": (t_mem + t_comp) * alpha}

@@ -123,3 +123,29 @@ def test_block_loops_keep_their_statements():
     # T_N = N, T_K = K with one h tile (the case of the five evaluated workloads when N fits a tile)
     one_h = pm.estimate("mhnk", dims, dict(tiles, h=64), batch=3, elem_bytes=2, W=1e12, P=1e14, n_units=100)
     assert one_h["mem_bytes"]["L_B"] == 12 * 32 * 128 * 2 and one_h["mem_bytes"]["L_D"] == 12 * 128 * 64 * 2
+
+
+def test_alpha_in_rounds():
+    """eq. (5) for blocks that run in rounds: hand-evaluated values, the cases where it is 1, its
+    relation to the printed form (never above it, equal to it only in the limit of one block
+    more than whole rounds), and the same estimate() otherwise."""
+    assert pm.alpha_rounds(256, 256) == 1.0 and pm.alpha_rounds(1024, 256) == 1.0     # whole rounds: nothing idle
+    assert pm.alpha_rounds(384, 256) == pytest.approx(512 / 384)                      # 2 rounds, the second half empty
+    assert pm.alpha_rounds(192, 256) == pytest.approx(256 / 192)                      # 1 round, a quarter of the units idle
+    assert pm.alpha_rounds(257, 256) == pytest.approx(512 / 257)
+    assert pm.alpha_rounds(32, 256) == 8.0
+    for nb in (1, 7, 255, 256, 257, 511, 512, 513, 5000):
+        for nu in (1, 64, 256, 1024):
+            a, printed = pm.alpha_rounds(nb, nu), (nb + nu) / nb
+            assert 1.0 <= a <= printed
+            assert (a == 1.0) == (nb % nu == 0)
+    # one block more than whole rounds approaches the printed form from below
+    assert pm.alpha_rounds(256 * 50 + 1, 256) == pytest.approx((256 * 51) / (256 * 50 + 1))
+    assert (256 * 50 + 1 + 256) / (256 * 50 + 1) - pm.alpha_rounds(256 * 50 + 1, 256) < 1e-4
+    dims = {"m": 512, "n": 512, "k": 64, "h": 64}
+    tiles = {"m": 128, "n": 64, "k": 64, "h": 64}
+    a = pm.estimate("mhnk", dims, tiles, 96, 2, W=8e12, P=2.5e15, n_units=256)
+    b = pm.estimate("mhnk", dims, tiles, 96, 2, W=8e12, P=2.5e15, n_units=256, rounds=True)
+    assert a["n_block"] == b["n_block"] == 384 and a["alpha"] == pytest.approx(640 / 384) and b["alpha"] == pytest.approx(512 / 384)
+    assert b["t_estm"] == pytest.approx((b["t_mem"] + b["t_comp"]) * 512 / 384)
+    assert (a["t_mem"], a["t_comp"]) == (b["t_mem"], b["t_comp"])
