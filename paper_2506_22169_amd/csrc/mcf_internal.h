@@ -12,9 +12,9 @@ constexpr double kHbmBytesPerSec = 8.0e12;    // W: HBM3E peak
 constexpr double kL2BytesPerSec = 32.0e12;    // bandwidth charged to re-reads served by L2/MALL
 constexpr double kMfmaFlopsPerSec = 2.5e15;   // P: dense fp16/bf16 MFMA peak
 constexpr int kComputeUnits = 256;            // compute units
-// eq. (5) in waves: a block counts with its waves, but at most 6 (measured: on one compute unit a
-// block of 8 waves delivers about 1.5x a block of 4, not 2x), and N_SM is 6 such units per CU.
-constexpr int kWaveUnitsPerBlock = 6;
+// eq. (5) in SIMDs: a block takes as many of a compute unit's four SIMDs as it has waves, at most
+// all four, and N_SM is four such units per compute unit.
+constexpr int kWaveUnitsPerBlock = 4;
 constexpr int kWaveUnits = kComputeUnits * kWaveUnitsPerBlock;
 constexpr int kLdsBytesPerBlock = 160 * 1024; // Shm_max of Rule 4
 constexpr int kVgprBudget = 512;              // arch + accumulation VGPRs per lane at 1 wave/SIMD

@@ -15,7 +15,7 @@ from paper_2506_22169_amd.binding import Problem, Tiles, make_problem
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 # machine constants the picker documents (MI355X): HBM and L2 bandwidth, MFMA peak, compute units
-W_HBM, W_L2, P_MFMA, CUS, WAVE_CAP = 8.0e12, 32.0e12, 2.5e15, 256, 6
+W_HBM, W_L2, P_MFMA, CUS, WAVE_CAP = 8.0e12, 32.0e12, 2.5e15, 256, 4
 LDS_MAX = 160 * 1024
 
 
@@ -107,9 +107,9 @@ def test_picker_terms_match_the_paper_model(name):
             assert t.tk == (w.K if w.K <= 256 and (w.K, tl) != (256, 128) and (w.K, tl) != (256, 64) else 128)
             tiles = {"m": t.tm, "n": t.tn, "k": t.tk, "h": tl}
             units_per_block = (t.waves + 3) // 4
-            # eq. (5) in waves: N_block = blocks x min(waves, 6), N_SM = 256 compute units x 6
+            # eq. (5) in rounds: a block takes min(waves, 4) of the four SIMDs of one of 256 compute units
             r = pm.estimate("mhnk", dims, tiles, w.batch, 2, W=W_HBM, P=P_MFMA,
-                            n_units=CUS * WAVE_CAP / min(t.waves, WAVE_CAP), W_reread=W_L2)
+                            n_units=CUS * WAVE_CAP // min(t.waves, WAVE_CAP), W_reread=W_L2, rounds=True)
             assert t.blocks == r["n_block"]
             assert t.compulsory_bytes == r["compulsory_bytes"] == w.compulsory_bytes
             assert t.model_bytes == r["model_bytes"]
