@@ -212,9 +212,6 @@ def main():
     per_set, flops = w.compulsory_bytes, w.flops
     P = w.L
     if args.chain3:                       # F[b, L, P] read once; G[b, M, P] replaces E[b, M, L] (P = L)
-        if args.tune:
-            print("bench.py: --chain3 takes the model's tiles or --tiles, not --tune", file=sys.stderr)
-            return 2
         f_bits = mi.to_bits(mi.draw(w.seed, 4, (w.batch, w.L, P), w.dist), w.dtype)
         F0 = dev(f_bits)
         per_set += 2 * w.batch * w.L * P
@@ -245,7 +242,7 @@ def main():
     prob = c_problem(w.batch, w.M, w.K, w.N, w.L, w.dtype,
                      b_stride=(w.N * w.K, 1, w.K) if w.softmax else None)
     search = None
-    if args.chain3 and tiles is None:
+    if args.chain3 and tiles is None and not args.tune:
         try:
             t3 = mcf.pick_tiles3(prob, P, w.softmax)
         except mcf.McfError:
@@ -259,7 +256,7 @@ def main():
 
         def measure(t):
             nonlocal tiles
-            tiles = (t.mb, t.rg, t.ns, t.nj, t.tl)
+            tiles = (t.mb, t.rg, t.ns, t.nj) if args.chain3 else (t.mb, t.rg, t.ns, t.nj, t.tl)
             reps = max(2 * n_sets, min(200, args.steps))
             for i in range(3):
                 step(i)
@@ -275,8 +272,15 @@ def main():
             e1.record()
             torch.cuda.synchronize()
             return e0.elapsed_time(e1) * 1e-3 / reps
-        best, rep = mcf.search_tiles(prob, w.softmax, measure, seed=w.seed)
-        tiles = (best.mb, best.rg, best.ns, best.nj, best.tl)
+        if args.chain3:
+            try:
+                best, rep = mcf.search_tiles3(prob, P, w.softmax, measure, seed=w.seed)
+            except mcf.McfError:
+                print(f"bench.py: no three-GEMM kernels built for K={w.K} L={w.L} P={P}", file=sys.stderr)
+                return 2
+        else:
+            best, rep = mcf.search_tiles(prob, w.softmax, measure, seed=w.seed)
+        tiles = (best.mb, best.rg, best.ns, best.nj) if args.chain3 else (best.mb, best.rg, best.ns, best.nj, best.tl)
         search = {"measured": rep.measured, "generations": rep.generations, "converged": bool(rep.converged),
                   "best_us": rep.best_t_s * 1e6,
                   "log": [[e.generation, e.mb, e.rg, e.ns, e.nj, e.tl, round(e.t_est_s * 1e6, 3), round(e.t_meas_s * 1e6, 3)]

@@ -245,6 +245,21 @@ int mcf_tune_tiles(const mcf_problem *problem, int softmax, float scale, const v
                    mcf_search_report *report_or_null);
 
 /*
+ * The same three calls for the three-GEMM chain (Sec. III-A: the analysis and with it the
+ * exploration carry over to longer chains): the candidates are the arrangements built for
+ * (K, L, P), ranked by the model terms of their two-GEMM part (the third GEMM adds the same
+ * work to each); mcf_tune_tiles3 measures mcf_gemm_chain3 with the arguments of that call.
+ */
+int mcf_list_candidates3(const mcf_problem *problem, int64_t P, int softmax, mcf_tiles *out, int cap);
+int mcf_search_tiles3(const mcf_problem *problem, int64_t P, int softmax,
+                      const mcf_search_params *params_or_null, mcf_measure_fn measure, void *user,
+                      mcf_tiles *best, mcf_search_report *report_or_null);
+int mcf_tune_tiles3(const mcf_problem *problem, int softmax, float scale, int64_t P,
+                    const int64_t *f_stride, const void *A, const void *B, const void *D,
+                    const void *F, void *G, const mcf_search_params *params_or_null, int launches,
+                    void *hip_stream, mcf_tiles *best, mcf_search_report *report_or_null);
+
+/*
  * Search-space generation and pruning (Sec. III-A, III-B, III-C).  Host only.  The paper's space
  * is (tiling expressions) x (tile sizes); the kernels of this library are points of what is left
  * of it after Rules 1-4, and these entry points say which.

@@ -115,6 +115,13 @@ def load_library():
     lib.mcf_gemm_chain3.argtypes = [PP, ctypes.c_int, ctypes.c_float, ctypes.c_int64, ctypes.POINTER(ctypes.c_int64),
                                     vp, vp, vp, vp, vp, TP, vp]
     lib.mcf_pick_tiles3.argtypes = [PP, ctypes.c_int64, ctypes.c_int, TP]
+    lib.mcf_list_candidates3.argtypes = [PP, ctypes.c_int64, ctypes.c_int, TP, ctypes.c_int]
+    lib.mcf_search_tiles3.argtypes = [PP, ctypes.c_int64, ctypes.c_int, ctypes.POINTER(SearchParams), MEASURE_FN, vp, TP,
+                                      ctypes.POINTER(SearchReport)]
+    lib.mcf_tune_tiles3.argtypes = [PP, ctypes.c_int, ctypes.c_float, ctypes.c_int64, ctypes.POINTER(ctypes.c_int64), vp, vp, vp,
+                                    vp, vp, ctypes.POINTER(SearchParams), ctypes.c_int, vp, TP, ctypes.POINTER(SearchReport)]
+    for f in (lib.mcf_list_candidates3, lib.mcf_search_tiles3, lib.mcf_tune_tiles3):
+        f.restype = ctypes.c_int
     lib.mcf_list_variants3.argtypes = [PP, ctypes.c_int64, ctypes.c_int, ctypes.POINTER(ctypes.c_int32), ctypes.c_int]
     lib.mcf_softmax_gemm_chain.argtypes = [PP, ctypes.c_float, vp, vp, vp, vp, TP, vp]
     lib.mcf_causal_softmax_gemm_chain.argtypes = [PP, ctypes.c_float, ctypes.c_int64, vp, vp, vp, vp, TP, vp]
@@ -306,7 +313,7 @@ def _search_params(population, top_n, epsilon, seed, max_generations):
     return sp
 
 
-def search_tiles(problem, softmax, measure, population=0, top_n=0, epsilon=0.0, seed=0, max_generations=0):
+def search_tiles(problem, softmax, measure, population=0, top_n=0, epsilon=0.0, seed=0, max_generations=0, P=0):
     """mcf_search_tiles: Alg. 1 with `measure(Tiles) -> seconds` as the measurement; zero
     parameters read as the library defaults.  Returns (Tiles, SearchReport)."""
     failure = []
@@ -320,12 +327,31 @@ def search_tiles(problem, softmax, measure, population=0, top_n=0, epsilon=0.0, 
 
     sp = _search_params(population, top_n, epsilon, seed, max_generations)
     best, rep = Tiles(), SearchReport()
-    st = load_library().mcf_search_tiles(ctypes.byref(problem), int(bool(softmax)), ctypes.byref(sp), MEASURE_FN(cb),
-                                         None, ctypes.byref(best), ctypes.byref(rep))
+    if P:
+        st = load_library().mcf_search_tiles3(ctypes.byref(problem), int(P), int(bool(softmax)), ctypes.byref(sp), MEASURE_FN(cb),
+                                              None, ctypes.byref(best), ctypes.byref(rep))
+    else:
+        st = load_library().mcf_search_tiles(ctypes.byref(problem), int(bool(softmax)), ctypes.byref(sp), MEASURE_FN(cb),
+                                             None, ctypes.byref(best), ctypes.byref(rep))
     if failure:
         raise failure[0]
     _check(st)
     return best, rep
+
+
+def search_tiles3(problem, P, softmax, measure, **kw):
+    """mcf_search_tiles3: Alg. 1 over the arrangements built for the three-GEMM chain."""
+    return search_tiles(problem, softmax, measure, P=P, **kw)
+
+
+def list_candidates3(problem, P, softmax=False):
+    """mcf_list_candidates3: the arrangements built for the three-GEMM chain with the model terms of
+    their two-GEMM part."""
+    lib = load_library()
+    n = lib.mcf_list_candidates3(ctypes.byref(problem), int(P), int(bool(softmax)), None, 0)
+    buf = (Tiles * max(n, 1))()
+    lib.mcf_list_candidates3(ctypes.byref(problem), int(P), int(bool(softmax)), buf, n)
+    return [buf[i] for i in range(n)]
 
 
 def tune_tiles(A, B, D, scale=None, out=None, launches=0, population=0, top_n=0, epsilon=0.0, seed=0,
@@ -346,7 +372,7 @@ def tune_tiles(A, B, D, scale=None, out=None, launches=0, population=0, top_n=0,
     return best, rep
 
 
-def gemm_chain3(A, B, D, F, scale=None, out=None, tiles=None, stream=None):
+def gemm_chain3(A, B, D, F, scale=None, out=None, tiles=None, stream=None, _tune=None):
     """mcf_gemm_chain3: G = ((A . B) . D) . F, or (softmax_rows(scale * A . B) . D) . F when scale is
     given, on device tensors; F[b,L,P] with unit column stride, G[b,M,P]."""
     import torch
@@ -374,11 +400,25 @@ def gemm_chain3(A, B, D, F, scale=None, out=None, tiles=None, stream=None):
     if F.shape[0] <= 1:
         sf[0] = 0
     fs = (ctypes.c_int64 * 3)(*sf)
+    ptrs = [ctypes.c_void_p(t.data_ptr()) for t in (A, B, D, F, out)]
+    if _tune is not None:      # mcf_tune_tiles3 over the same arguments
+        sp = _search_params(*_tune["search"])
+        best, rep = Tiles(), SearchReport()
+        _check(lib.mcf_tune_tiles3(ctypes.byref(p), int(scale is not None), ctypes.c_float(0.0 if scale is None else scale),
+                                   ctypes.c_int64(P), fs, *ptrs, ctypes.byref(sp), int(_tune["launches"]), _stream_ptr(stream),
+                                   ctypes.byref(best), ctypes.byref(rep)))
+        return best, rep
     _check(lib.mcf_gemm_chain3(ctypes.byref(p), int(scale is not None), ctypes.c_float(0.0 if scale is None else scale),
-                               ctypes.c_int64(P), fs, ctypes.c_void_p(A.data_ptr()), ctypes.c_void_p(B.data_ptr()),
-                               ctypes.c_void_p(D.data_ptr()), ctypes.c_void_p(F.data_ptr()), ctypes.c_void_p(out.data_ptr()),
-                               _tiles_arg(tiles), _stream_ptr(stream)))
+                               ctypes.c_int64(P), fs, *ptrs, _tiles_arg(tiles), _stream_ptr(stream)))
     return out
+
+
+def tune_tiles3(A, B, D, F, scale=None, out=None, launches=0, population=0, top_n=0, epsilon=0.0, seed=0,
+                max_generations=0, stream=None):
+    """mcf_tune_tiles3: Alg. 1 measured on the device for the three-GEMM chain over these tensors.
+    `out` is overwritten.  Returns (Tiles, SearchReport)."""
+    return gemm_chain3(A, B, D, F, scale=scale, out=out, stream=stream,
+                       _tune={"search": (population, top_n, epsilon, seed, max_generations), "launches": launches})
 
 
 class _MetaLike:

@@ -105,13 +105,13 @@ static const Variant *find_variant3(int dtype, int64_t K, int64_t L, int64_t P, 
     return nullptr;
 }
 
-// Tile choice for the three-GEMM chain: the arrangement (among those built for it) whose
-// two-GEMM part the model ranks best (ties broken as for the two-GEMM chain); the third GEMM
-// adds the same work to each of them.
-static int pick3(const mcf_problem *p, int softmax, int b_kcontig, int64_t P, mcf_tiles *out) {
+// The arrangements built for the three-GEMM chain on (dtype, K, L, P, layout of B), each with
+// the model terms of its two-GEMM part (the third GEMM adds the same work to all of them) and
+// the LDS bytes of the three-GEMM kernel, in registry order.
+int candidates3(const mcf_problem *p, int softmax, int b_kcontig, int64_t P, std::vector<mcf_tiles> *out) {
     int n = 0;
     const Variant *v = variants3(&n);
-    bool have = false;
+    out->clear();
     for (int i = 0; i < n; ++i) {
         if (v[i].dtype != p->in_dtype || v[i].K != p->K || v[i].L != p->L || v[i].P != P ||
             v[i].softmax != (softmax != 0) || v[i].b_kcontig != b_kcontig || v[i].scratch_bytes != 0)
@@ -122,9 +122,22 @@ static int pick3(const mcf_problem *p, int softmax, int b_kcontig, int64_t P, mc
         const int st = mcf_eval_tiles(p, softmax, &t);
         if (st != MCF_OK && st != MCF_EINVAL) continue;
         t.lds_bytes = lds_bytes_for(&v[i]); // with the F tile
-        if (!have || better(t, *out)) { *out = t; have = true; }
+        out->push_back(t);
     }
-    return have ? MCF_OK : MCF_EUNSUPPORTED;
+    return out->empty() ? MCF_EUNSUPPORTED : MCF_OK;
+}
+
+// Tile choice for the three-GEMM chain: the arrangement (among those built for it) whose
+// two-GEMM part the model ranks best (ties broken as for the two-GEMM chain); the third GEMM
+// adds the same work to each of them.
+static int pick3(const mcf_problem *p, int softmax, int b_kcontig, int64_t P, mcf_tiles *out) {
+    std::vector<mcf_tiles> c;
+    const int st = candidates3(p, softmax, b_kcontig, P, &c);
+    if (st != MCF_OK) return st;
+    *out = c[0];
+    for (const mcf_tiles &t : c)
+        if (better(t, *out)) *out = t;
+    return MCF_OK;
 }
 
 // P == 0: the two-GEMM chain into E[b, M, L].  P > 0: the three-GEMM chain; F[b, L, P] with
@@ -270,6 +283,28 @@ extern "C" int mcf_pick_tiles3(const mcf_problem *p, int64_t P, int softmax, mcf
     const int st = mcf::decode_layout(&pc, &lay);
     if (st != MCF_OK) return st;
     return mcf::pick3(&pc, softmax != 0, lay.b_kcontig, P, out);
+}
+
+namespace mcf {
+// Problem of the two-GEMM part and layout of B for a three-GEMM problem (e_stride describes G).
+int problem3(const mcf_problem *p, int64_t P, mcf_problem *pc, int *b_kcontig) {
+    mcf::Layout lay;
+    if (!p || P <= 0) return MCF_EINVAL;
+    *pc = *p;
+    memset(pc->e_stride, 0, sizeof(pc->e_stride));
+    const int st = mcf::decode_layout(pc, &lay);
+    if (st == MCF_OK) *b_kcontig = lay.b_kcontig;
+    return st;
+}
+} // namespace mcf
+
+extern "C" int mcf_list_candidates3(const mcf_problem *p, int64_t P, int softmax, mcf_tiles *out, int cap) {
+    mcf_problem pc;
+    int bk = 0;
+    std::vector<mcf_tiles> c;
+    if (mcf::problem3(p, P, &pc, &bk) != MCF_OK || mcf::candidates3(&pc, softmax != 0, bk, P, &c) != MCF_OK) return 0;
+    for (int i = 0; i < (int)c.size() && out && i < cap; ++i) out[i] = c[i];
+    return (int)c.size();
 }
 
 extern "C" int mcf_list_variants3(const mcf_problem *p, int64_t P, int softmax, int32_t *out, int cap) {

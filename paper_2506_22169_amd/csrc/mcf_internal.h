@@ -96,6 +96,11 @@ int vgpr_estimate(int K, int L, int mb, int rg, int ns, int nj, int softmax, int
 // Feasible candidates for a problem, with their model terms, in registry order (the set
 // mcf_pick_tiles chooses from).  MCF_OK, or the status mcf_pick_tiles would return.
 int feasible_candidates(const mcf_problem *p, int softmax, std::vector<mcf_tiles> *out);
+// The same for the three-GEMM chain: problem3() strips the output's strides (they describe G) and
+// finds the layout of B, candidates3() lists the arrangements built for (K, L, P) with the model
+// terms of their two-GEMM part.
+int problem3(const mcf_problem *p, int64_t P, mcf_problem *two_gemm_part, int *b_kcontig);
+int candidates3(const mcf_problem *p, int softmax, int b_kcontig, int64_t P, std::vector<mcf_tiles> *out);
 
 void set_last_error(const char *msg);
 

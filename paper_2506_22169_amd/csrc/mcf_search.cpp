@@ -154,12 +154,9 @@ class TileSearch {
 
 using namespace mcf;
 
-extern "C" int mcf_search_tiles(const mcf_problem *p, int softmax, const mcf_search_params *params,
-                                mcf_measure_fn measure, void *user, mcf_tiles *best, mcf_search_report *report) {
-    if (!measure || !best) return MCF_EINVAL;
-    std::vector<mcf_tiles> space;
-    const int st = feasible_candidates(p, softmax, &space);
-    if (st != MCF_OK) return st;
+// Alg. 1 over a given space of candidates.
+static int search_space(std::vector<mcf_tiles> space, const mcf_search_params *params, mcf_measure_fn measure, void *user,
+                        mcf_tiles *best, mcf_search_report *report) {
     const int members = params && params->population > 0 ? params->population : 32;
     const int shortlist = params && params->top_n > 0 ? params->top_n : 8;
     const int max_gen = params && params->max_generations > 0 ? params->max_generations : 16;
@@ -196,6 +193,27 @@ extern "C" int mcf_search_tiles(const mcf_problem *p, int softmax, const mcf_sea
     return MCF_OK;
 }
 
+extern "C" int mcf_search_tiles(const mcf_problem *p, int softmax, const mcf_search_params *params,
+                                mcf_measure_fn measure, void *user, mcf_tiles *best, mcf_search_report *report) {
+    if (!measure || !best) return MCF_EINVAL;
+    std::vector<mcf_tiles> space;
+    const int st = feasible_candidates(p, softmax, &space);
+    if (st != MCF_OK) return st;
+    return search_space(std::move(space), params, measure, user, best, report);
+}
+
+extern "C" int mcf_search_tiles3(const mcf_problem *p, int64_t P, int softmax, const mcf_search_params *params,
+                                 mcf_measure_fn measure, void *user, mcf_tiles *best, mcf_search_report *report) {
+    if (!measure || !best) return MCF_EINVAL;
+    mcf_problem pc;
+    int bk = 0;
+    std::vector<mcf_tiles> space;
+    int st = problem3(p, P, &pc, &bk);
+    if (st == MCF_OK) st = candidates3(&pc, softmax != 0, bk, P, &space);
+    if (st != MCF_OK) return st;
+    return search_space(std::move(space), params, measure, user, best, report);
+}
+
 namespace {
 
 struct DeviceMeasure {
@@ -208,11 +226,15 @@ struct DeviceMeasure {
     hipStream_t stream;
     hipEvent_t e0, e1;
     int status; // first failure seen by the callback
+    int64_t P;  // > 0: the three-GEMM chain, with F and its strides
+    const int64_t *f_stride;
+    const void *F;
 };
 
 double measure_on_device(const mcf_tiles *cand, void *user) {
     DeviceMeasure *m = (DeviceMeasure *)user;
     auto launch = [&]() {
+        if (m->P > 0) return mcf_gemm_chain3(m->p, m->softmax, m->scale, m->P, m->f_stride, m->A, m->B, m->D, m->F, m->E, cand, m->stream);
         return m->softmax ? mcf_softmax_gemm_chain(m->p, m->scale, m->A, m->B, m->D, m->E, cand, m->stream)
                           : mcf_gemm_chain(m->p, m->A, m->B, m->D, m->E, cand, m->stream);
     };
@@ -235,13 +257,16 @@ double measure_on_device(const mcf_tiles *cand, void *user) {
 
 } // namespace
 
-extern "C" int mcf_tune_tiles(const mcf_problem *p, int softmax, float scale, const void *A, const void *B,
-                              const void *D, void *E, const mcf_search_params *params, int launches, void *stream,
-                              mcf_tiles *best, mcf_search_report *report) {
+// Alg. 1 measured on the device, for the two-GEMM chain (P == 0) or the three-GEMM chain.
+static int tune(const mcf_problem *p, int softmax, float scale, int64_t P, const int64_t *f_stride, const void *A,
+                const void *B, const void *D, const void *F, void *E, const mcf_search_params *params, int launches,
+                void *stream, mcf_tiles *best, mcf_search_report *report) {
     if (!p || !best) return MCF_EINVAL;
+    auto pick = [&](mcf_tiles *t) { return P > 0 ? mcf_pick_tiles3(p, P, softmax, t) : mcf_pick_tiles(p, softmax, t); };
     // an empty problem has nothing to measure: fall back on the model
-    if (p->batch == 0 || p->M == 0 || p->L == 0 || p->N == 0) return mcf_pick_tiles(p, softmax, best);
-    DeviceMeasure m{p, softmax != 0, scale, A, B, D, E, launches > 0 ? launches : 20, (hipStream_t)stream, nullptr, nullptr, MCF_OK};
+    if (p->batch == 0 || p->M == 0 || p->L == 0 || p->N == 0) return pick(best);
+    DeviceMeasure m{p, softmax != 0, scale, A, B, D, E, launches > 0 ? launches : 20, (hipStream_t)stream, nullptr, nullptr, MCF_OK,
+                    P, f_stride, F};
     hipError_t err = hipEventCreate(&m.e0);
     if (err == hipSuccess) err = hipEventCreate(&m.e1);
     if (err != hipSuccess) {
@@ -252,7 +277,7 @@ extern "C" int mcf_tune_tiles(const mcf_problem *p, int softmax, float scale, co
     // bring the clocks up before the first candidate is timed: a few hundred launches of the
     // model's choice (or 50 ms, whichever comes first)
     mcf_tiles warm;
-    int st = mcf_pick_tiles(p, softmax, &warm);
+    int st = pick(&warm);
     if (st == MCF_OK) {
         const double t1 = measure_on_device(&warm, &m);
         if (t1 > 0.0) {
@@ -261,10 +286,26 @@ extern "C" int mcf_tune_tiles(const mcf_problem *p, int softmax, float scale, co
             for (int r = 0; r < rounds && m.status == MCF_OK; ++r) (void)measure_on_device(&warm, &m);
         }
     }
-    if (st == MCF_OK && m.status == MCF_OK) st = mcf_search_tiles(p, softmax, params, measure_on_device, &m, best, report);
+    if (st == MCF_OK && m.status == MCF_OK)
+        st = P > 0 ? mcf_search_tiles3(p, P, softmax, params, measure_on_device, &m, best, report)
+                   : mcf_search_tiles(p, softmax, params, measure_on_device, &m, best, report);
     else if (st == MCF_OK) st = MCF_ELAUNCH;
     if (st == MCF_ELAUNCH && m.status != MCF_OK) st = m.status; // the chain call's own verdict (EINVAL, EALIGN, ...)
     (void)hipEventDestroy(m.e0);
     (void)hipEventDestroy(m.e1);
     return st;
+}
+
+extern "C" int mcf_tune_tiles(const mcf_problem *p, int softmax, float scale, const void *A, const void *B,
+                              const void *D, void *E, const mcf_search_params *params, int launches, void *stream,
+                              mcf_tiles *best, mcf_search_report *report) {
+    return tune(p, softmax, scale, 0, nullptr, A, B, D, nullptr, E, params, launches, stream, best, report);
+}
+
+extern "C" int mcf_tune_tiles3(const mcf_problem *p, int softmax, float scale, int64_t P, const int64_t *f_stride,
+                               const void *A, const void *B, const void *D, const void *F, void *G,
+                               const mcf_search_params *params, int launches, void *stream, mcf_tiles *best,
+                               mcf_search_report *report) {
+    if (P <= 0) return MCF_EINVAL;
+    return tune(p, softmax, scale, P, f_stride, A, B, D, F, G, params, launches, stream, best, report);
 }

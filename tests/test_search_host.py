@@ -89,3 +89,36 @@ def test_defaults_and_errors():
     assert e.value.status == 2
     lib = mcf.load_library()
     assert lib.mcf_search_tiles(ctypes.byref(prob), 0, None, ctypes.cast(None, mcf.binding.MEASURE_FN), None, None, None) == 1
+
+
+@pytest.mark.parametrize("KLP,softmax,N,n,seed", [((64, 64, 64), False, 32, 8, 1), ((128, 128, 128), True, 6, 2, 7),
+                                                   ((64, 128, 128), False, 12, 3, 11), ((64, 64, 128), True, 4, 1, 3)])
+def test_three_gemm_search_equals_oracle_search(KLP, softmax, N, n, seed):
+    """mcf_search_tiles3: the same algorithm over the arrangements built for the three-GEMM chain
+    (candidates and estimates from mcf_list_candidates3, which the picker test covers)."""
+    K, L, P = KLP
+    prob = make_problem(8, 1024, K, 1024, L, "f16", b_stride=(1024 * K, 1, K) if softmax else None)
+    tiles = mcf.list_candidates3(prob, P, softmax)
+    shapes = [(t.mb, t.rg, t.ns, t.nj, t.tl) for t in tiles]
+    assert len(shapes) >= 4 and [s[:4] for s in shapes] == [s for s in mcf.list_variants3(prob, P, softmax) if s in [x[:4] for x in shapes]]
+    pick = mcf.pick_tiles3(prob, P, softmax)
+    assert pick.t_est_s == min(t.t_est_s for t in tiles)
+    table = _table(shapes, tiles, 300 + seed)
+    space = [((mb, rg), (ns, nj), (tl,)) for (mb, rg, ns, nj, tl) in shapes]
+    est = [t.t_est_s for t in tiles]
+    want = sr.heuristic_search(space, est, lambda c: table[shapes[c]], N=N, n=n, epsilon=0.02, seed=seed, max_generations=16)
+    calls = []
+
+    def measure(t):
+        calls.append((t.mb, t.rg, t.ns, t.nj, t.tl))
+        return table[(t.mb, t.rg, t.ns, t.nj, t.tl)]
+
+    best, rep = mcf.search_tiles3(prob, P, softmax, measure, population=N, top_n=n, epsilon=0.02, seed=seed, max_generations=16)
+    assert rep.space == len(shapes)
+    assert calls == [shapes[c] for _, c, _, _ in want["log"]]
+    assert (rep.generations, bool(rep.converged)) == (want["generations"], want["converged"])
+    fastest = min(want["log"], key=lambda e: e[3])
+    assert (best.mb, best.rg, best.ns, best.nj, best.tl) == shapes[fastest[1]] and rep.best_t_s == fastest[3]
+    with pytest.raises(mcf.McfError) as e:                       # no three-GEMM kernels for this P
+        mcf.search_tiles3(prob, 32, softmax, measure)
+    assert e.value.status == 2
