@@ -696,7 +696,10 @@ void chain_kernel(const KParams p) {
             stage_c = stage_c + 1 == S ? 0 : stage_c + 1;
         }
     } else if constexpr (PIPE) {
-        // Software pipeline over n-tiles.  A wave's matrix work and its softmax arithmetic sit on
+        // Software pipeline over n-tiles (softmax chains; plain chains with K and L of 32, where a
+        // tile is only a handful of MFMAs per wave and the pipeline is what keeps them coming: the
+        // conversion of tile i then rides behind GEMM 1 of tile i+1).
+        // A wave's matrix work and its softmax arithmetic sit on
         // different pipes of the SIMD, but only overlap when they alternate in ONE wave's
         // instruction stream (an MFMA of 32 cycles hides five to six ordinary vector operations
         // or three exponentials issued behind it; two waves a phase apart mostly queue up).  So
@@ -721,30 +724,31 @@ void chain_kernel(const KParams p) {
         float mx[MB], mneg[MB], corr[MB], sum0[MB], sum1[MB];
 
         // element e of a row set <-> slice j = e / 16, accumulator register r = e % 16
+        // (a plain chain has no softmax: its slices are the mask of a ragged tile and the conversion)
         auto vstep = [&](auto kc, auto curc, int n0) __attribute__((always_inline)) {
             constexpr int k = decltype(kc)::value, CUR = decltype(curc)::value;
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
-                if constexpr (k < TA) {
-                    if constexpr (k == 0) {
-                        // a ragged last tile, or a tile on or beyond the mask's edge: columns a row does
-                        // not see contribute nothing (tiles before the last are whole in memory, so
-                        // without a mask the test only ever holds for the last)
-                        if (n0 + 32 * NJ > n_clean) {
-                            // element e sits 32(e/16) + 8((e%16)/4) + e%4 columns right of the lane's first;
-                            // one compare and one select per element, in order (the pin keeps the
-                            // compiler from forming all the compares first, a scalar register pair each)
-                            const int room = sees(wrow0 + 32 * mb + c) - n0 - 4 * g; // columns the row sees from there on
+                if constexpr (k == 0) {
+                    // a ragged last tile, or a tile on or beyond the mask's edge: columns a row does
+                    // not see contribute nothing (tiles before the last are whole in memory, so
+                    // without a mask the test only ever holds for the last)
+                    if (n0 + 32 * NJ > n_clean) {
+                        // element e sits 32(e/16) + 8((e%16)/4) + e%4 columns right of the lane's first;
+                        // one compare and one select per element, in order (the pin keeps the
+                        // compiler from forming all the compares first, a scalar register pair each)
+                        const int room = sees(wrow0 + 32 * mb + c) - n0 - 4 * g; // columns the row sees from there on
 #pragma unroll
-                            for (int e = 0; e < NE; ++e) {
-                                float x = cc[CUR][e / 16][mb][e % 16];
-                                x = 32 * (e / 16) + 8 * ((e % 16) / 4) + (e % 4) < room ? x : -INFINITY;
-                                pin(x);
-                                cc[CUR][e / 16][mb][e % 16] = x;
-                            }
+                        for (int e = 0; e < NE; ++e) {
+                            float x = cc[CUR][e / 16][mb][e % 16];
+                            x = 32 * (e / 16) + 8 * ((e % 16) / 4) + (e % 4) < room ? x : (SOFTMAX ? -INFINITY : 0.f);
+                            pin(x);
+                            cc[CUR][e / 16][mb][e % 16] = x;
                         }
-                        mx[mb] = cc[CUR][0][mb][0];
                     }
+                }
+                if constexpr (SOFTMAX && k < TA) {
+                    if constexpr (k == 0) mx[mb] = cc[CUR][0][mb][0];
 #pragma unroll
                     for (int e = k * EA; e < (k + 1) * EA && e < NE; ++e) mx[mb] = fmaxf(mx[mb], cc[CUR][e / 16][mb][e % 16]);
                     pin(mx[mb]);
@@ -762,7 +766,7 @@ void chain_kernel(const KParams p) {
                         sum0[mb] = 0.f;
                         sum1[mb] = 0.f;
                     }
-                } else {
+                } else if constexpr (SOFTMAX) {
 #pragma unroll
                     for (int e = (k - TA) * EB; e < (k - TA + 1) * EB && e < NE; ++e) {
                         float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(cc[CUR][e / 16][mb][e % 16], c1, mneg[mb]));
@@ -775,12 +779,12 @@ void chain_kernel(const KParams p) {
                     pin(sum1[mb]);
                 }
                 if constexpr (k >= T2) {
-                    // elements whose exponential was issued in an earlier step, spread evenly over
-                    // the steps of GEMM 1; the last step takes what is left
-                    constexpr int done_prev = k - 1 < TA ? 0 : ((k - TA) * EB < NE ? (k - TA) * EB : NE);
+                    // elements that are final (softmax: whose exponential was issued in an earlier
+                    // step), spread evenly over the steps of GEMM 1; the last step takes what is left
+                    constexpr int done_prev = !SOFTMAX ? NE : (k - 1 < TA ? 0 : ((k - TA) * EB < NE ? (k - TA) * EB : NE));
                     constexpr int quota = NE * (k - T2 + 1) / T1;
                     constexpr int hi = k == TT - 1 ? NE : ((done_prev < quota ? done_prev : quota) & ~1);
-                    constexpr int done_prev2 = k - 2 < TA ? 0 : ((k - 1 - TA) * EB < NE ? (k - 1 - TA) * EB : NE);
+                    constexpr int done_prev2 = !SOFTMAX ? NE : (k - 2 < TA ? 0 : ((k - 1 - TA) * EB < NE ? (k - 1 - TA) * EB : NE));
                     constexpr int quota2 = NE * (k - T2) / T1;
                     constexpr int lo = k == T2 ? 0 : ((done_prev2 < quota2 ? done_prev2 : quota2) & ~1);
 #pragma unroll
@@ -846,7 +850,7 @@ void chain_kernel(const KParams p) {
         // tiles before it, GEMM 2 of the previous tile included) brought to the new reference
         auto settle = [&]() __attribute__((always_inline)) {
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
+            for (int mb = 0; SOFTMAX && mb < MB; ++mb) {
                 l_run[mb] = l_run[mb] * corr[mb] + (sum0[mb] + sum1[mb]);
                 if (__builtin_amdgcn_ballot_w64(corr[mb] != 1.0f)) {
 #pragma unroll

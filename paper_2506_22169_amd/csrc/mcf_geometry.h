@@ -102,7 +102,7 @@ constexpr int pick_stages(int K, int L, int mb, int rg, int ns, int nj, int budg
 // blocks can share the 160 KiB LDS of a compute unit (measured: a deeper ring that costs the
 // second resident block loses more than it gains).
 constexpr int kLdsRingBudget = 80 * 1024;
-// Softmax chains run a software pipeline over three consecutive n-tiles: in iteration i a wave
+// Softmax chains (and the plain chains named below) run a software pipeline over three consecutive n-tiles: in iteration i a wave
 // issues the MFMAs of GEMM 2 of tile i-1 and of GEMM 1 of tile i+1 with the softmax arithmetic of
 // tile i spread between them, so tiles i-1, i and i+1 are live and tile i+2 is landing: a ring of
 // 4 (measured: a deeper one is slower, by up to a fifth on the short attention shapes).
@@ -110,7 +110,11 @@ constexpr int kLdsRingBudget = 80 * 1024;
 // softmax loop then runs the phases one after the other, see skewed_groups).  `extra` = LDS held
 // beside the ring (the F tile of a three-GEMM chain).
 constexpr int pipe_stages(int K, int L, int mb, int rg, int ns, int nj, bool softmax, bool ksplit = false, int extra = 0) {
-    if (!softmax || ksplit) return 0;
+    if (ksplit) return 0;
+    // plain chains: only where K and L are 32, in blocks of 8 waves that own at most two row sets
+    // each (measured on 16 x [4096,32].[32,1024].[1024,32]: 3-4 % faster for (1,8,1,2) and (2,4,2,2),
+    // no change for (1,4,2,2), a third slower for (4,2,4,1); with K = L = 64 slower throughout)
+    if (!softmax && !(K <= 32 && L <= 32 && mb <= 2 && rg * ns == 8)) return 0;
     return total_lds_bytes(K, L, mb, rg, ns, nj, 4) + extra <= 160 * 1024 ? 4 : 0;
 }
 // Waves per SIMD a pipelined softmax kernel is compiled for.  A block brings rg*ns/4 of them; a

@@ -61,9 +61,9 @@ int vgpr_estimate(int K, int L, int mb, int rg, int ns, int nj, int softmax, int
     const int slot = ksplit ? ksplit_slot_bytes(K, L, mb, rg, 32 * ns * nj) : stage_bytes(K, L, 32 * ns * nj);
     const int loads = (ksplit ? 2 : 1) * ((slot / 1024 + rg * ns - 1) / (rg * ns));
     const int hb = h_blocks(L);
-    // a pipelined softmax chain holds C of two consecutive n-tiles and the exponentials of one
+    // a pipelined chain holds C of two consecutive n-tiles and the 16-bit P of one
     // (and fetches its LDS operands two MFMA steps ahead instead of a GEMM at a time)
-    const bool piped = softmax && !ksplit;
+    const bool piped = pipe_stages(K, L, mb, rg, ns, nj, softmax != 0, ksplit != 0) > 0;
     const int c_tiles = piped ? nj * mb * (16 + 16 + 8) : nj * mb * (16 + 8);
     const int operands = piped ? 16 : (K / 16) * 4 + hb * 8;
     return mb * (K / 16) * 4 + mb * hb * 16 + c_tiles + operands + loads + 24 + (softmax ? 16 : 0);
